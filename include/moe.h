@@ -1,0 +1,132 @@
+/*
+ * moe.h: C ABI of the expert-side hot path of one Mixture-of-Experts layer on one MI355X (gfx950).
+ *
+ * The four hot calls follow the paper's statement of the MoE layer (Section 2.2: gating scores,
+ * top-k routing, expert FFNs, weighted sum of the selected experts' outputs), the steps its
+ * implementation section lists for the fused gating kernel (Section 6 "Fused kernels": top-k
+ * selection, number of tokens per expert, normalised token weights, scatter to experts) and the
+ * two expert GEMMs of its GEMM table (Section 4.2, Table 3: "FFN Input", "FFN Output"):
+ *
+ *     moe_route -> moe_dispatch -> moe_expert_ffn -> moe_combine
+ *
+ * Conventions for every call below
+ *   - Notation: T tokens, d hidden size (paper: h), f expert intermediate size (paper: h'),
+ *     E experts, k experts per token (paper: K), A = T*k assignments.
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller, row-major and contiguous,
+ *     16-byte aligned. The library allocates no device memory and keeps no device state: each
+ *     call is a pure function of its arguments, so calls on different streams never share
+ *     anything but their arguments.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream). All work is enqueued
+ *     on it; no call synchronises the device or copies anything to the host. The per-expert
+ *     sizes stay on the device (`offsets` is read by the kernels).
+ *   - x, xp, h, y, out and the expert weights share cfg.dtype (float32 or bfloat16). Router
+ *     logits and token weights are always float32; index arrays are int32.
+ *   - Errors: argument errors (null pointer, T < 0, T > T_max, misaligned pointer) are detected
+ *     on the host before anything is launched and leave the outputs untouched; a failed launch
+ *     returns MOE_ERR_HIP. moe_last_error() gives a message for the last failure on that ctx.
+ *     T == 0 is MOE_OK; moe_route then still writes counts = 0 and offsets = 0.
+ *   - A moe_ctx is not thread-safe; use one per host thread.
+ */
+#ifndef MOE_H
+#define MOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct moe_ctx moe_ctx; /* opaque; host memory only */
+
+typedef enum {
+  MOE_OK = 0,
+  MOE_ERR_INVALID_ARG = 1,
+  MOE_ERR_UNSUPPORTED = 2, /* shape or dtype outside what the kernels are built for */
+  MOE_ERR_HIP = 3          /* a HIP call or launch failed */
+} moe_status;
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
+
+typedef struct {
+  int32_t T_max; /* largest T any call will be given */
+  int32_t d;     /* hidden size; multiple of 128 */
+  int32_t f;     /* expert intermediate size; multiple of 128 */
+  int32_t E;     /* experts, 1..256 */
+  int32_t k;     /* experts per token, 1..min(E, 64) */
+  int32_t dtype; /* moe_dtype */
+} moe_config;
+
+/* Validate cfg and build a context (host memory only). MOE_ERR_INVALID_ARG for a null
+ * pointer or non-positive sizes, MOE_ERR_UNSUPPORTED for sizes outside the limits above. */
+moe_status moe_create(const moe_config* cfg, moe_ctx** out);
+void moe_destroy(moe_ctx* ctx);
+/* Message of the last failed call on ctx ("" if none). Valid until the next call on ctx. */
+const char* moe_last_error(const moe_ctx* ctx);
+const char* moe_status_string(moe_status s);
+
+/* Bytes of the packed expert-weight buffer moe_pack_weights writes (0 if cfg is invalid). */
+size_t moe_packed_weight_bytes(const moe_config* cfg);
+
+/*
+ * One-time weight pre-pack (expert weights are static while serving). Canonical layout in:
+ *   w_gate[E, f, d], w_up[E, f, d], w_down[E, d, f]     (each expert's matrix is [out, in],
+ * so Table 3's (h, h') "FFN Input" parameter is used as x * W^T). Out: `packed`, the layout the
+ * FFN kernels stream (bf16: tiles in matrix-core operand order; f32: plain concatenation).
+ * `packed` must hold moe_packed_weight_bytes(cfg) bytes and must not overlap the inputs.
+ */
+moe_status moe_pack_weights(moe_ctx* ctx, const void* w_gate, const void* w_up, const void* w_down,
+                            void* packed, void* stream);
+
+/*
+ * Routing (Section 2.2; Section 6 "Fused kernels"). In: logits[T, E] float32.
+ * Out: topk_idx[T, k]  the k experts with the largest logits, largest first; equal logits are
+ *                      ordered by ascending expert index (so ties go to the lower index)
+ *      topk_w[T, k]    softmax over those k logits (float32)
+ *      counts[E]       assignments per expert
+ *      offsets[E + 1]  exclusive prefix sum of counts; offsets[E] = T*k
+ * NaN logits rank as -inf. Indices, counts and offsets are exact integers.
+ */
+moe_status moe_route(moe_ctx* ctx, int32_t T, const float* logits, int32_t* topk_idx, float* topk_w,
+                     int32_t* counts, int32_t* offsets, void* stream);
+
+/*
+ * Dispatch pack (Section 2.2 "send input tokens to the experts"; Section 6 "scatter tokens to
+ * respective experts"): stable counting sort of the A assignments by expert.
+ * In: x[T, d], topk_idx[T, k], offsets[E + 1] (as written by moe_route).
+ * Out: xp[A, d]   expert-contiguous copy of the tokens: rows offsets[e]..offsets[e+1]-1 belong
+ *                 to expert e, in ascending flat assignment order t*k + j
+ *      pos[T, k]  row of assignment (t, j)
+ *      src[A]     flat assignment index t*k + j that owns row r  (pos and src are inverse
+ *                 permutations of each other)
+ * Entries of topk_idx outside [0, E) are skipped (their pos/src/xp entries stay unwritten).
+ */
+moe_status moe_dispatch(moe_ctx* ctx, int32_t T, const void* x, const int32_t* topk_idx,
+                        const int32_t* offsets, void* xp, int32_t* pos, int32_t* src, void* stream);
+
+/*
+ * Expert FFN as a grouped SwiGLU GEMM (Section 4.2, Table 3; tensor-parallel degree 1):
+ * for every expert e and row r in [offsets[e], offsets[e+1]):
+ *     h[r, :] = silu(xp[r, :] * W_gate_e^T) .* (xp[r, :] * W_up_e^T)      ("FFN Input", fused)
+ *     y[r, :] = h[r, :] * W_down_e^T                                       ("FFN Output")
+ * In: xp[A, d], offsets[E + 1], packed weights from moe_pack_weights.
+ * Workspace: h_ws[A, f] in cfg.dtype (caller-owned; holds h afterwards). Out: y[A, d].
+ * bf16: products accumulate in float32; h and y are rounded to bf16 (nearest-even) when stored.
+ * Experts with no rows cost nothing (their weights are not read).
+ */
+moe_status moe_expert_ffn(moe_ctx* ctx, int32_t T, const void* xp, const int32_t* offsets,
+                          const void* packed_w, void* h_ws, void* y, void* stream);
+
+/*
+ * Combine (Section 2.2: the layer output is the weighted sum of the selected experts' outputs):
+ *     out[t, :] = sum_{j = 0..k-1} topk_w[t, j] * y[pos[t, j], :]     (float32 sum, j ascending)
+ * In: y[A, d], pos[T, k], topk_w[T, k]. Out: out[T, d] in cfg.dtype.
+ * Entries of pos outside [0, A) contribute nothing.
+ */
+moe_status moe_combine(moe_ctx* ctx, int32_t T, const void* y, const int32_t* pos, const float* topk_w,
+                       void* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_H */

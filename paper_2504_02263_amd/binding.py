@@ -1,0 +1,203 @@
+"""ctypes binding of the C ABI in include/moe.h.
+
+Argument marshalling only: every step of the path runs in the HIP kernels of
+libmoe_gfx950.so. PyTorch is used for device memory and streams, nothing else. There is no
+CPU fallback: if the library is missing and cannot be built, importing callers get an error.
+
+The functions mirror the C entry points (moe_create, moe_pack_weights, moe_route,
+moe_dispatch, moe_expert_ffn, moe_combine); `MoEPath` strings the four hot calls together
+over buffers it allocates once.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch  # imported before the library so both share one HIP runtime (same SONAME)
+
+from . import build as _build
+
+MOE_OK, MOE_ERR_INVALID_ARG, MOE_ERR_UNSUPPORTED, MOE_ERR_HIP = 0, 1, 2, 3
+MOE_F32, MOE_BF16 = 0, 1
+_DTYPES = {"f32": (MOE_F32, torch.float32), "bf16": (MOE_BF16, torch.bfloat16)}
+
+EXPORTS = ("moe_create", "moe_destroy", "moe_last_error", "moe_status_string", "moe_packed_weight_bytes",
+           "moe_pack_weights", "moe_route", "moe_dispatch", "moe_expert_ffn", "moe_combine")
+
+
+class MoeConfig(ctypes.Structure):
+    _fields_ = [("T_max", ctypes.c_int32), ("d", ctypes.c_int32), ("f", ctypes.c_int32),
+                ("E", ctypes.c_int32), ("k", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+
+
+class MoeError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"moe status {status}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libmoe_gfx950.so (building it first only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB_PATH):
+        _build.build()
+    lib = ctypes.CDLL(_build.LIB_PATH)
+    vp, i32, cfgp = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(MoeConfig)
+    lib.moe_create.argtypes = [cfgp, ctypes.POINTER(vp)]
+    lib.moe_create.restype = ctypes.c_int
+    lib.moe_destroy.argtypes = [vp]
+    lib.moe_destroy.restype = None
+    lib.moe_last_error.argtypes = [vp]
+    lib.moe_last_error.restype = ctypes.c_char_p
+    lib.moe_status_string.argtypes = [ctypes.c_int]
+    lib.moe_status_string.restype = ctypes.c_char_p
+    lib.moe_packed_weight_bytes.argtypes = [cfgp]
+    lib.moe_packed_weight_bytes.restype = ctypes.c_size_t
+    lib.moe_pack_weights.argtypes = [vp] + [vp] * 4 + [vp]
+    lib.moe_route.argtypes = [vp, i32] + [vp] * 5 + [vp]
+    lib.moe_dispatch.argtypes = [vp, i32] + [vp] * 6 + [vp]
+    lib.moe_expert_ffn.argtypes = [vp, i32] + [vp] * 5 + [vp]
+    lib.moe_combine.argtypes = [vp, i32] + [vp] * 4 + [vp]
+    for name in ("moe_pack_weights", "moe_route", "moe_dispatch", "moe_expert_ffn", "moe_combine"):
+        getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _ptr(t) -> Optional[int]:
+    """Device address of a tensor (or a raw int address, or None)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _check(ctx, status: int):
+    if status != MOE_OK:
+        lib = load_library()
+        msg = lib.moe_last_error(ctx).decode() if ctx else ""
+        raise MoeError(status, f"{lib.moe_status_string(status).decode()} {msg}".strip())
+
+
+def moe_create(T_max: int, d: int, f: int, E: int, k: int, dtype: str) -> int:
+    lib = load_library()
+    cfg = MoeConfig(T_max, d, f, E, k, _DTYPES[dtype][0])
+    ctx = ctypes.c_void_p()
+    status = lib.moe_create(ctypes.byref(cfg), ctypes.byref(ctx))
+    if status != MOE_OK:
+        raise MoeError(status, lib.moe_status_string(status).decode())
+    return ctx.value
+
+
+def moe_destroy(ctx: int) -> None:
+    load_library().moe_destroy(ctx)
+
+
+def moe_packed_weight_bytes(T_max: int, d: int, f: int, E: int, k: int, dtype: str) -> int:
+    cfg = MoeConfig(T_max, d, f, E, k, _DTYPES[dtype][0])
+    return load_library().moe_packed_weight_bytes(ctypes.byref(cfg))
+
+
+def moe_pack_weights(ctx, w_gate, w_up, w_down, packed, stream=None) -> None:
+    _check(ctx, load_library().moe_pack_weights(ctx, _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(packed),
+                                                _stream(stream)))
+
+
+def moe_route(ctx, T, logits, topk_idx, topk_w, counts, offsets, stream=None) -> None:
+    _check(ctx, load_library().moe_route(ctx, T, _ptr(logits), _ptr(topk_idx), _ptr(topk_w), _ptr(counts),
+                                         _ptr(offsets), _stream(stream)))
+
+
+def moe_dispatch(ctx, T, x, topk_idx, offsets, xp, pos, src, stream=None) -> None:
+    _check(ctx, load_library().moe_dispatch(ctx, T, _ptr(x), _ptr(topk_idx), _ptr(offsets), _ptr(xp), _ptr(pos),
+                                            _ptr(src), _stream(stream)))
+
+
+def moe_expert_ffn(ctx, T, xp, offsets, packed_w, h_ws, y, stream=None) -> None:
+    _check(ctx, load_library().moe_expert_ffn(ctx, T, _ptr(xp), _ptr(offsets), _ptr(packed_w), _ptr(h_ws), _ptr(y),
+                                              _stream(stream)))
+
+
+def moe_combine(ctx, T, y, pos, topk_w, out, stream=None) -> None:
+    _check(ctx, load_library().moe_combine(ctx, T, _ptr(y), _ptr(pos), _ptr(topk_w), _ptr(out), _stream(stream)))
+
+
+class MoEPath:
+    """Buffers for one (T_max, d, f, E, k, dtype) layer plus the four hot calls over them."""
+
+    def __init__(self, T_max: int, d: int, f: int, E: int, k: int, dtype: str, device="cuda:0"):
+        if not torch.cuda.is_available():
+            raise RuntimeError("MoEPath needs a GPU: there is no CPU path")
+        self.T_max, self.d, self.f, self.E, self.k, self.dtype = T_max, d, f, E, k, dtype
+        self.device = torch.device(device)
+        self.tdtype = _DTYPES[dtype][1]
+        self.ctx = moe_create(T_max, d, f, E, k, dtype)
+        A = max(T_max * k, 1)
+        dev, i32 = self.device, torch.int32
+        self.topk_idx = torch.empty((max(T_max, 1), k), dtype=i32, device=dev)
+        self.topk_w = torch.empty((max(T_max, 1), k), dtype=torch.float32, device=dev)
+        self.counts = torch.empty(E, dtype=i32, device=dev)
+        self.offsets = torch.empty(E + 1, dtype=i32, device=dev)
+        self.xp = torch.empty((A, d), dtype=self.tdtype, device=dev)
+        self.pos = torch.empty((max(T_max, 1), k), dtype=i32, device=dev)
+        self.src = torch.empty(A, dtype=i32, device=dev)
+        self.h = torch.empty((A, f), dtype=self.tdtype, device=dev)
+        self.y = torch.empty((A, d), dtype=self.tdtype, device=dev)
+        self.out = torch.empty((max(T_max, 1), d), dtype=self.tdtype, device=dev)
+        self.packed = None
+
+    def close(self):
+        if self.ctx:
+            moe_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def pack_weights(self, w_gate, w_up, w_down, stream=None):
+        """w_gate/w_up [E, f, d], w_down [E, d, f] device tensors in the layer dtype."""
+        nbytes = moe_packed_weight_bytes(self.T_max, self.d, self.f, self.E, self.k, self.dtype)
+        self.packed = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        moe_pack_weights(self.ctx, w_gate, w_up, w_down, self.packed, stream)
+        return self.packed
+
+    def route(self, logits, T=None, stream=None):
+        T = logits.shape[0] if T is None else T
+        moe_route(self.ctx, T, logits, self.topk_idx, self.topk_w, self.counts, self.offsets, stream)
+
+    def dispatch(self, x, T=None, stream=None):
+        T = x.shape[0] if T is None else T
+        moe_dispatch(self.ctx, T, x, self.topk_idx, self.offsets, self.xp, self.pos, self.src, stream)
+
+    def expert_ffn(self, T, stream=None):
+        moe_expert_ffn(self.ctx, T, self.xp, self.offsets, self.packed, self.h, self.y, stream)
+
+    def combine(self, T, stream=None):
+        moe_combine(self.ctx, T, self.y, self.pos, self.topk_w, self.out, stream)
+
+    def forward(self, x, logits, stream=None):
+        """One pass of the whole hot path; returns out[:T] (a view of the preallocated buffer)."""
+        T = x.shape[0]
+        self.route(logits, T, stream)
+        self.dispatch(x, T, stream)
+        self.expert_ffn(T, stream)
+        self.combine(T, stream)
+        return self.out[:T]

@@ -1,0 +1,144 @@
+// C ABI entry points: argument validation on the host, then the kernel launchers.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+#include <new>
+#include "moe_internal.h"
+
+namespace {
+
+moe_status fail(moe_ctx* ctx, moe_status s, const char* fmt, ...) {
+  if (ctx) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+    va_end(ap);
+  }
+  return s;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+moe_status check_config(const moe_config* c, const char** why) {
+  *why = "";
+  if (c->T_max < 0 || c->d <= 0 || c->f <= 0 || c->E <= 0 || c->k <= 0) {
+    *why = "T_max, d, f, E, k must be positive (T_max may be 0)";
+    return MOE_ERR_INVALID_ARG;
+  }
+  if (c->k > c->E) { *why = "k > E"; return MOE_ERR_INVALID_ARG; }
+  if (c->dtype != MOE_F32 && c->dtype != MOE_BF16) { *why = "unknown dtype"; return MOE_ERR_INVALID_ARG; }
+  if (c->E > moe::kMaxExperts) { *why = "E > 256"; return MOE_ERR_UNSUPPORTED; }
+  if (c->k > moe::kMaxTopK) { *why = "k > 64"; return MOE_ERR_UNSUPPORTED; }
+  if (c->d % 128 || c->f % 128) { *why = "d and f must be multiples of 128"; return MOE_ERR_UNSUPPORTED; }
+  if ((int64_t)c->T_max * c->k > (int64_t)1 << 24) { *why = "T_max * k > 2^24"; return MOE_ERR_UNSUPPORTED; }
+  if ((int64_t)c->E * c->d * c->f > (int64_t)1 << 36) { *why = "E*d*f too large"; return MOE_ERR_UNSUPPORTED; }
+  return MOE_OK;
+}
+
+// Common per-call checks; `ptrs` are all the tensor pointers of the call.
+moe_status check_call(moe_ctx* ctx, const char* fn, int32_t T, const void* const* ptrs, int n) {
+  if (!ctx) return MOE_ERR_INVALID_ARG;
+  ctx->err[0] = 0;
+  if (T < 0 || T > ctx->cfg.T_max)
+    return fail(ctx, MOE_ERR_INVALID_ARG, "%s: T = %d outside [0, T_max = %d]", fn, T, ctx->cfg.T_max);
+  for (int i = 0; i < n; ++i) {
+    if (!ptrs[i]) return fail(ctx, MOE_ERR_INVALID_ARG, "%s: tensor pointer %d is null", fn, i);
+    if (!aligned16(ptrs[i])) return fail(ctx, MOE_ERR_INVALID_ARG, "%s: tensor pointer %d is not 16-byte aligned", fn, i);
+  }
+  return MOE_OK;
+}
+
+moe_status finish(moe_ctx* ctx, const char* fn, hipError_t err) {
+  if (err == hipSuccess) return MOE_OK;
+  return fail(ctx, MOE_ERR_HIP, "%s: %s", fn, hipGetErrorString(err));
+}
+
+int elem_bytes(const moe_ctx* ctx) { return ctx->cfg.dtype == MOE_BF16 ? 2 : 4; }
+
+}  // namespace
+
+extern "C" {
+
+moe_status moe_create(const moe_config* cfg, moe_ctx** out) {
+  if (!cfg || !out) return MOE_ERR_INVALID_ARG;
+  *out = nullptr;
+  const char* why;
+  const moe_status s = check_config(cfg, &why);
+  if (s != MOE_OK) return s;
+  moe_ctx* ctx = new (std::nothrow) moe_ctx;
+  if (!ctx) return MOE_ERR_INVALID_ARG;
+  ctx->cfg = *cfg;
+  ctx->err[0] = 0;
+  *out = ctx;
+  return MOE_OK;
+}
+
+void moe_destroy(moe_ctx* ctx) { delete ctx; }
+
+const char* moe_last_error(const moe_ctx* ctx) { return ctx ? ctx->err : "null context"; }
+
+const char* moe_status_string(moe_status s) {
+  switch (s) {
+    case MOE_OK: return "MOE_OK";
+    case MOE_ERR_INVALID_ARG: return "MOE_ERR_INVALID_ARG";
+    case MOE_ERR_UNSUPPORTED: return "MOE_ERR_UNSUPPORTED";
+    case MOE_ERR_HIP: return "MOE_ERR_HIP";
+  }
+  return "unknown moe_status";
+}
+
+size_t moe_packed_weight_bytes(const moe_config* cfg) {
+  const char* why;
+  if (!cfg || check_config(cfg, &why) != MOE_OK) return 0;
+  return moe::packed_weight_bytes(*cfg);
+}
+
+moe_status moe_pack_weights(moe_ctx* ctx, const void* w_gate, const void* w_up, const void* w_down, void* packed,
+                            void* stream) {
+  const void* ptrs[] = {w_gate, w_up, w_down, packed};
+  const moe_status s = check_call(ctx, "moe_pack_weights", 0, ptrs, 4);
+  if (s != MOE_OK) return s;
+  return finish(ctx, "moe_pack_weights",
+                moe::launch_pack_weights(ctx->cfg, w_gate, w_up, w_down, packed, static_cast<hipStream_t>(stream)));
+}
+
+moe_status moe_route(moe_ctx* ctx, int32_t T, const float* logits, int32_t* topk_idx, float* topk_w, int32_t* counts,
+                     int32_t* offsets, void* stream) {
+  const void* ptrs[] = {logits, topk_idx, topk_w, counts, offsets};
+  const moe_status s = check_call(ctx, "moe_route", T, ptrs, 5);
+  if (s != MOE_OK) return s;
+  return finish(ctx, "moe_route",
+                moe::launch_route(logits, T, ctx->cfg.E, ctx->cfg.k, topk_idx, topk_w, counts, offsets,
+                                  static_cast<hipStream_t>(stream)));
+}
+
+moe_status moe_dispatch(moe_ctx* ctx, int32_t T, const void* x, const int32_t* topk_idx, const int32_t* offsets,
+                        void* xp, int32_t* pos, int32_t* src, void* stream) {
+  const void* ptrs[] = {x, topk_idx, offsets, xp, pos, src};
+  const moe_status s = check_call(ctx, "moe_dispatch", T, ptrs, 6);
+  if (s != MOE_OK) return s;
+  return finish(ctx, "moe_dispatch",
+                moe::launch_dispatch(x, topk_idx, offsets, T, ctx->cfg.E, ctx->cfg.k, ctx->cfg.d * elem_bytes(ctx), xp,
+                                     pos, src, static_cast<hipStream_t>(stream)));
+}
+
+moe_status moe_expert_ffn(moe_ctx* ctx, int32_t T, const void* xp, const int32_t* offsets, const void* packed_w,
+                          void* h_ws, void* y, void* stream) {
+  const void* ptrs[] = {xp, offsets, packed_w, h_ws, y};
+  const moe_status s = check_call(ctx, "moe_expert_ffn", T, ptrs, 5);
+  if (s != MOE_OK) return s;
+  return finish(ctx, "moe_expert_ffn",
+                moe::launch_expert_ffn(ctx->cfg, T, xp, offsets, packed_w, h_ws, y, static_cast<hipStream_t>(stream)));
+}
+
+moe_status moe_combine(moe_ctx* ctx, int32_t T, const void* y, const int32_t* pos, const float* topk_w, void* out,
+                       void* stream) {
+  const void* ptrs[] = {y, pos, topk_w, out};
+  const moe_status s = check_call(ctx, "moe_combine", T, ptrs, 4);
+  if (s != MOE_OK) return s;
+  return finish(ctx, "moe_combine",
+                moe::launch_combine(y, pos, topk_w, T, ctx->cfg.k, ctx->cfg.d, ctx->cfg.dtype, out,
+                                    static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

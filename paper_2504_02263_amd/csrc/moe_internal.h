@@ -1,0 +1,30 @@
+// Internal declarations shared by the translation units of the MoE library (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "moe.h"
+
+struct moe_ctx {
+  moe_config cfg;
+  char err[256];
+};
+
+namespace moe {
+
+constexpr int kMaxExperts = 256;   // experts held one per thread of a 256-thread workgroup
+constexpr int kMaxTopK = 64;       // one wavefront lane per pick
+
+// Each launcher enqueues its kernels on `stream` and returns hipGetLastError().
+hipError_t launch_route(const float* logits, int T, int E, int k, int32_t* topk_idx, float* topk_w,
+                        int32_t* counts, int32_t* offsets, hipStream_t stream);
+hipError_t launch_dispatch(const void* x, const int32_t* topk_idx, const int32_t* offsets, int T, int E, int k,
+                           int row_bytes, void* xp, int32_t* pos, int32_t* src, hipStream_t stream);
+hipError_t launch_combine(const void* y, const int32_t* pos, const float* topk_w, int T, int k, int d,
+                          int dtype, void* out, hipStream_t stream);
+hipError_t launch_pack_weights(const moe_config& cfg, const void* w_gate, const void* w_up, const void* w_down,
+                               void* packed, hipStream_t stream);
+hipError_t launch_expert_ffn(const moe_config& cfg, int T, const void* xp, const int32_t* offsets,
+                             const void* packed, void* h, void* y, hipStream_t stream);
+size_t packed_weight_bytes(const moe_config& cfg);
+
+}  // namespace moe

@@ -1,0 +1,231 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs. Integer outputs (indices, counts, offsets, permutations, copied rows) must be bit-exact;
+token weights within 1e-6; floating-point tensors within relative Frobenius error 1e-5 (fp32) or
+1e-2 (bf16)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as O
+from paper_2504_02263_amd import binding as B
+from workloads import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 1e-2}
+W_TOL = 1e-6   # |w_gpu - w_oracle|: fp32 exp/div on weights <= 1 (a few ulp) vs the float64 oracle
+
+
+def dev(a: np.ndarray) -> torch.Tensor:
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t: torch.Tensor) -> np.ndarray:
+    """Device tensor -> numpy at storage precision (bf16 comes back as uint16 bits)."""
+    if t.dtype == torch.bfloat16:
+        return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def rel_fro(gpu: np.ndarray, ref: np.ndarray) -> float:
+    g = O.widen(gpu)
+    den = np.linalg.norm(ref)
+    return float(np.linalg.norm(g - ref) / den) if den > 0 else float(np.linalg.norm(g))
+
+
+def small_cfg(T, d, f, E, k, dtype):
+    return synth.LayerConfig(f"t{T}_{d}_{f}_{E}_{k}_{dtype}", T=T, d=d, f=f, E=E, k=k, dtype=dtype, router="logits")
+
+
+def run_layer(cfg, x, logits, W, T_max=None):
+    """Full path on the GPU; returns the MoEPath (buffers hold every intermediate)."""
+    path = B.MoEPath(T_max or max(cfg.T, 1), cfg.d, cfg.f, cfg.E, cfg.k, cfg.dtype)
+    path.pack_weights(dev(W[0]), dev(W[1]), dev(W[2]))
+    path.forward(dev(x), dev(logits))
+    torch.cuda.synchronize()
+    return path
+
+
+def check_integers(path, ref, T, k):
+    A = T * k
+    assert (host(path.topk_idx)[:T] == ref["topk_idx"]).all()
+    assert (host(path.counts) == ref["counts"]).all()
+    assert (host(path.offsets) == ref["offsets"]).all()
+    assert (host(path.pos)[:T] == ref["pos"]).all()
+    assert (host(path.src)[:A] == ref["src"]).all()
+    assert (host(path.xp)[:A] == ref["xp"]).all()                 # rows are copied bit for bit
+    np.testing.assert_allclose(host(path.topk_w)[:T], ref["topk_w"], rtol=0, atol=W_TOL)
+
+
+# ------------------------------------------------------------------------------- route
+
+@pytest.mark.parametrize("T,E,k", [(1, 8, 2), (64, 8, 2), (257, 8, 1), (1000, 16, 4), (513, 32, 4), (700, 64, 6),
+                                   (300, 5, 5), (129, 100, 7), (64, 256, 8), (33, 3, 2), (4096, 8, 2), (0, 8, 2)])
+def test_route_bit_exact(T, E, k):
+    rng = np.random.default_rng(T * 1000 + E * 10 + k)
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    if T > 8:
+        logits[::5] = rng.integers(-1, 2, size=logits[::5].shape).astype(np.float32)   # heavy ties
+        logits[1] = 0.0
+        logits[2] = np.arange(E, dtype=np.float32)
+        logits[3] = -np.arange(E, dtype=np.float32)
+        logits[4, : E // 2] = -0.0
+        logits[4, E // 2:] = 0.0
+    idx, w, counts, offsets = O.route(logits, k)
+    ctx = B.moe_create(max(T, 1), 128, 128, E, k, "f32")
+    g_idx = torch.full((max(T, 1), k), -7, dtype=torch.int32, device="cuda")
+    g_w = torch.zeros((max(T, 1), k), dtype=torch.float32, device="cuda")
+    g_counts = torch.full((E,), -7, dtype=torch.int32, device="cuda")
+    g_offsets = torch.full((E + 1,), -7, dtype=torch.int32, device="cuda")
+    B.moe_route(ctx, T, dev(logits) if T else torch.zeros(4, device="cuda"), g_idx, g_w, g_counts, g_offsets)
+    torch.cuda.synchronize()
+    B.moe_destroy(ctx)
+    assert (host(g_idx)[:T] == idx).all()
+    assert (host(g_counts) == counts).all()
+    assert (host(g_offsets) == offsets).all()
+    np.testing.assert_allclose(host(g_w)[:T], w, rtol=0, atol=W_TOL)
+    if T:
+        np.testing.assert_allclose(host(g_w)[:T].sum(1), 1.0, rtol=0, atol=4e-7)
+
+
+# ------------------------------------------------------------------------------- dispatch / combine
+
+@pytest.mark.parametrize("T,E,k,d,dtype", [(64, 8, 2, 256, "f32"), (1000, 16, 4, 128, "bf16"), (777, 64, 6, 384, "bf16"),
+                                           (5000, 8, 2, 128, "f32"), (3, 4, 1, 128, "bf16"), (2731, 64, 6, 256, "bf16")])
+def test_dispatch_and_combine(T, E, k, d, dtype):
+    cfg = small_cfg(T, d, 128, E, k, dtype)
+    x = synth.make_activations(cfg, 3)
+    logits = synth.make_logits(cfg, 3)
+    logits[:, E - 1] = -50.0 if E > k else logits[:, E - 1]        # one empty expert where possible
+    idx, w, counts, offsets = O.route(logits, k)
+    xp, pos, src = O.dispatch(x, idx, offsets)
+    path = B.MoEPath(T, d, 128, E, k, dtype)
+    path.route(dev(logits))
+    path.dispatch(dev(x))
+    torch.cuda.synchronize()
+    A = T * k
+    assert (host(path.pos) == pos).all()
+    assert (host(path.src)[:A] == src).all()
+    assert (host(path.xp)[:A] == xp).all()
+    first = (host(path.pos).copy(), host(path.src).copy())
+    for _ in range(3):                                            # same answer every time (no atomics-order effects)
+        path.dispatch(dev(x))
+    torch.cuda.synchronize()
+    assert (host(path.pos) == first[0]).all() and (host(path.src) == first[1]).all()
+    # identity experts: y := xp, so combine must return x (weights sum to 1)
+    path.y.copy_(path.xp)
+    path.combine(T)
+    torch.cuda.synchronize()
+    ref = O.combine(xp, pos, w)
+    assert rel_fro(host(path.out), ref) <= (1e-6 if dtype == "f32" else 4e-3)
+    assert rel_fro(host(path.out), O.widen(x)) <= (1e-6 if dtype == "f32" else 4e-3)
+    # a real weighted sum of unrelated rows
+    yy = synth.make_activations(small_cfg(A, d, 128, E, k, dtype), 9)
+    path.y.copy_(dev(yy))
+    path.combine(T)
+    torch.cuda.synchronize()
+    assert rel_fro(host(path.out), O.combine(yy, pos, host(path.topk_w))) <= (1e-6 if dtype == "f32" else 4e-3)
+    path.close()
+
+
+# ------------------------------------------------------------------------------- expert FFN
+
+FFN_CASES = [
+    # T, d, f, E, k, dtype : spans every m-tile height (mean rows/expert 10..350), both ring depths
+    (40, 256, 512, 8, 2, "bf16"), (160, 256, 512, 8, 2, "bf16"), (320, 256, 512, 8, 2, "bf16"),
+    (800, 256, 512, 8, 2, "bf16"), (700, 384, 640, 4, 2, "bf16"), (100, 384, 128, 16, 4, "bf16"),
+    (333, 128, 384, 64, 6, "bf16"), (64, 256, 512, 8, 2, "f32"), (300, 128, 384, 5, 3, "f32"),
+]
+
+
+@pytest.mark.parametrize("T,d,f,E,k,dtype", FFN_CASES)
+def test_layer_small(T, d, f, E, k, dtype):
+    cfg = small_cfg(T, d, f, E, k, dtype)
+    x = synth.make_activations(cfg, 1)
+    logits = synth.make_logits(cfg, 1)
+    if E > k + 1:
+        logits[:, 1] = -60.0                                       # expert 1 gets no tokens
+    W = synth.make_all_expert_weights(cfg, 1, workers=4)
+    ref = O.moe_layer(x, logits, k, lambda e: (W[0][e], W[1][e], W[2][e]))
+    y_ref, h_ref = O.expert_ffn(ref["xp"], ref["offsets"], lambda e: (W[0][e], W[1][e], W[2][e]), return_h=True)
+    path = run_layer(cfg, x, logits, W)
+    A = T * k
+    check_integers(path, ref, T, k)
+    tol = TOL[dtype]
+    eh, ey, eo = rel_fro(host(path.h)[:A], h_ref), rel_fro(host(path.y)[:A], y_ref), rel_fro(host(path.out)[:T], ref["out"])
+    print(f"{cfg.name}: rel-Frobenius h {eh:.2e}  y {ey:.2e}  out {eo:.2e}")
+    assert eh <= tol and ey <= tol and eo <= tol
+    path.close()
+
+
+def test_ffn_arbitrary_offsets_and_smaller_T_than_T_max():
+    """moe_expert_ffn is a function of (xp, offsets) alone: very uneven hand-made segments."""
+    d, f, E, k = 256, 384, 6, 1
+    sizes = [0, 5, 0, 600, 1, 33]
+    A = sum(sizes)
+    offsets = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    cfg = small_cfg(A, d, f, E, k, "bf16")
+    xp = synth.make_activations(cfg, 5)
+    W = synth.make_all_expert_weights(cfg, 5, workers=4)
+    y_ref, h_ref = O.expert_ffn(xp, offsets, lambda e: (W[0][e], W[1][e], W[2][e]), return_h=True)
+    path = B.MoEPath(A + 100, d, f, E, k, "bf16")
+    path.pack_weights(dev(W[0]), dev(W[1]), dev(W[2]))
+    path.xp[:A].copy_(dev(xp))
+    path.offsets.copy_(dev(offsets))
+    path.y.fill_(7.0)
+    path.expert_ffn(A)
+    torch.cuda.synchronize()
+    assert rel_fro(host(path.h)[:A], h_ref) <= 1e-2
+    assert rel_fro(host(path.y)[:A], y_ref) <= 1e-2
+    assert (path.y[A:] == 7.0).all()                               # nothing written past the last row
+    path.close()
+
+
+def test_tiny_fp32_config():
+    """The tiny fp32 layer: logits from the gating matrix (computed once, on the host, and routed by both sides)."""
+    cfg = synth.CONFIGS["tiny_fp32"]
+    x = synth.make_activations(cfg)
+    logits = O.gate_logits(x, synth.make_router_weight(cfg))
+    W = synth.make_all_expert_weights(cfg, 0, workers=4)
+    ref = O.moe_layer(x, logits, cfg.k, lambda e: (W[0][e], W[1][e], W[2][e]))
+    path = run_layer(cfg, x, logits, W)
+    check_integers(path, ref, cfg.T, cfg.k)
+    err = rel_fro(host(path.out), ref["out"])
+    print(f"tiny_fp32: rel-Frobenius out {err:.2e}")
+    assert err <= 1e-5
+    path.close()
+
+
+def test_empty_batch():
+    path = B.MoEPath(16, 128, 128, 8, 2, "bf16")
+    path.packed = torch.zeros(B.moe_packed_weight_bytes(16, 128, 128, 8, 2, "bf16"), dtype=torch.uint8, device="cuda")
+    path.counts.fill_(-1)
+    path.offsets.fill_(-1)
+    x = torch.zeros((0, 128), dtype=torch.bfloat16, device="cuda")
+    path.route(torch.zeros(4, device="cuda"), T=0)
+    path.dispatch(path.xp, T=0)
+    path.expert_ffn(0)
+    path.combine(0)
+    torch.cuda.synchronize()
+    assert (path.counts == 0).all() and (path.offsets == 0).all()
+    path.close()
+
+
+def test_calls_run_on_the_given_stream():
+    cfg = small_cfg(200, 256, 256, 8, 2, "bf16")
+    x, logits = synth.make_activations(cfg, 2), synth.make_logits(cfg, 2)
+    W = synth.make_all_expert_weights(cfg, 2, workers=4)
+    ref = O.moe_layer(x, logits, cfg.k, lambda e: (W[0][e], W[1][e], W[2][e]))
+    path = B.MoEPath(cfg.T, cfg.d, cfg.f, cfg.E, cfg.k, cfg.dtype)
+    path.pack_weights(dev(W[0]), dev(W[1]), dev(W[2]))
+    xd, ld = dev(x), dev(logits)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        path.forward(xd, ld)           # binding picks up torch's current stream
+    path.forward(xd, ld, stream=s)     # and an explicit one
+    s.synchronize()
+    assert rel_fro(host(path.out), ref["out"]) <= 1e-2
+    path.close()

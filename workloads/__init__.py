@@ -13,5 +13,8 @@ from .synth import (  # noqa: F401
     make_logits,
     make_router_weight,
     make_expert_weights,
+    make_all_expert_weights,
+    zipf_bias,
+    MIXTRAL_SWEEP_T,
     microbatch_ranges,
 )

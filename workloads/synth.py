@@ -150,3 +150,24 @@ def microbatch_ranges(T: int, m: int) -> List[Tuple[int, int]]:
         out.append((start, start + n))
         start += n
     return out
+
+
+def make_all_expert_weights(cfg: LayerConfig, seed: int = 0, workers: int = 8):
+    """All experts' weights stacked: (W_gate[E,f,d], W_up[E,f,d], W_down[E,d,f]).
+
+    Same values as make_expert_weights(cfg, seed, e) for every e; experts are drawn in
+    parallel threads (each has its own stream, so the result does not depend on `workers`).
+    """
+    from concurrent.futures import ThreadPoolExecutor
+
+    np_dtype = np.float32 if cfg.dtype == "f32" else np.uint16
+    wg = np.empty((cfg.E, cfg.f, cfg.d), dtype=np_dtype)
+    wu = np.empty((cfg.E, cfg.f, cfg.d), dtype=np_dtype)
+    wd = np.empty((cfg.E, cfg.d, cfg.f), dtype=np_dtype)
+
+    def one(e: int):
+        wg[e], wu[e], wd[e] = make_expert_weights(cfg, seed, e)
+
+    with ThreadPoolExecutor(max_workers=max(1, workers)) as pool:
+        list(pool.map(one, range(cfg.E)))
+    return wg, wu, wd
