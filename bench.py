@@ -1,0 +1,229 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE hot path on one MI355X.
+
+A step is one pass of the whole path (moe_route -> moe_dispatch -> moe_ffn_input -> moe_ffn_output
+-> moe_combine) over one batch of seeded synthetic input that is already resident in HBM. The
+default workload is the Mixtral-8x22B-shaped decode micro-batch (d=6144, f=16384, E=8, top-2,
+bf16, T=256), the configuration the headline metric is quoted on.
+
+Prints ONE JSON line (see README/DESIGN for the fields). `roofline` is for the dominant kernel
+(the fused gate|up "FFN Input" GEMM): algorithmic bytes or flops per launch over its average
+duration, measured with events on the launch stream inside the timed region. `cpu_baseline` is
+the CPU oracle, as it stands, timed on this machine's host cores on a bounded sample.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--sweep] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+
+def dev(a, torch):
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def upload_and_pack(cfg, seed, path, torch, synth):
+    """Generate the expert weights on the host, upload, pre-pack once (outside any timed region)."""
+    t0 = time.time()
+    W = synth.make_all_expert_weights(cfg, seed, workers=min(16, os.cpu_count() or 8))
+    gen_s = time.time() - t0
+    wg, wu, wd = (dev(w, torch) for w in W)
+    path.pack_weights(wg, wu, wd)
+    torch.cuda.synchronize()
+    del wg, wu, wd
+    torch.cuda.empty_cache()
+    return W, gen_s
+
+
+def make_inputs(cfg, seed, synth):
+    """Activations and router logits. The gating GEMM is not part of the timed path, so for the
+    layer whose tests route through a gating matrix the logits are simply drawn here."""
+    return synth.make_activations(cfg, seed), synth.make_logits(cfg, seed)
+
+
+def time_workload(cfg, path, x_d, logits_d, steps, warmup, torch, R):
+    """W warm-up steps, then exactly K timed steps between device synchronisations."""
+    T = cfg.T
+    stream = torch.cuda.current_stream()
+
+    def step(ev=None):
+        path.route(logits_d, T, stream)
+        path.dispatch(x_d, T, stream)
+        if ev is not None:
+            ev[0].record(stream)
+        path.ffn_input(T, stream)
+        if ev is not None:
+            ev[1].record(stream)
+        path.ffn_output(T, stream)
+        path.combine(T, stream)
+
+    for _ in range(warmup):
+        step()
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    ffn_in_ms = float(np.mean([a.elapsed_time(b) for a, b in events]))
+
+    # per-call breakdown (separate, untimed pass)
+    names = ["route", "dispatch", "ffn_input", "ffn_output", "combine"]
+    calls = [lambda: path.route(logits_d, T, stream), lambda: path.dispatch(x_d, T, stream),
+             lambda: path.ffn_input(T, stream), lambda: path.ffn_output(T, stream), lambda: path.combine(T, stream)]
+    reps = max(5, min(steps, 20))
+    acc = {n: [] for n in names}
+    for _ in range(reps):
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)]
+        evs[0].record(stream)
+        for i, c in enumerate(calls):
+            c()
+            evs[i + 1].record(stream)
+        torch.cuda.synchronize()
+        for i, n in enumerate(names):
+            acc[n].append(evs[i].elapsed_time(evs[i + 1]))
+    calls_ms = {n: float(np.median(v)) for n, v in acc.items()}
+
+    counts = path.counts.cpu().numpy()
+    active = int((counts > 0).sum())
+    s = 2 if cfg.dtype == "bf16" else 4
+    cost = R.layer_cost(T, cfg.d, cfg.f, cfg.E, cfg.k, s, active_experts=active)
+    return ms_per_step, ffn_in_ms, calls_ms, counts, cost
+
+
+def roofline_entry(cfg, cost, ffn_in_ms, R):
+    t = ffn_in_ms * 1e-3
+    if cfg.dtype == "bf16":
+        peak_flops, unit_f = R.MI355X_BF16_DENSE_FLOPS, "TFLOP/s"
+    else:
+        peak_flops, unit_f = R.MI355X_FP32_VECTOR_FLOPS, "TFLOP/s"
+    t_mem = cost.ffn_in_bytes / R.MI355X_HBM_BYTES_PER_S
+    t_cmp = cost.ffn_in_flops / peak_flops
+    if t_mem >= t_cmp:
+        achieved, peak, unit, bound = cost.ffn_in_bytes / t / 1e9, R.MI355X_HBM_BYTES_PER_S / 1e9, "GB/s", "hbm"
+    else:
+        achieved, peak, unit = cost.ffn_in_flops / t / 1e12, peak_flops / 1e12, unit_f
+        bound = "mfma" if cfg.dtype == "bf16" else "alu"
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{cfg.name}.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("ffn_input_hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+    return {"kernel": "ffn_input (fused gate|up GEMM + SiLU*up)", "bound": bound, "achieved": round(achieved, 2),
+            "peak": peak, "unit": unit, "frac": round(achieved / peak, 4), "traffic": traffic,
+            "algorithmic_bytes": cost.ffn_in_bytes, "algorithmic_flops": cost.ffn_in_flops,
+            "avg_launch_ms": round(ffn_in_ms, 5)}
+
+
+def cpu_baseline(cfg, seed, W, x, logits, oracle_mod, sample_tokens):
+    """The oracle's whole layer on the first `sample_tokens` tokens of the same batch."""
+    n = min(sample_tokens, cfg.T)
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = 1
+    t0 = time.perf_counter()
+    oracle_mod.moe_layer(x[:n], logits[:n], cfg.k, lambda e: (W[0][e], W[1][e], W[2][e]))
+    dt = time.perf_counter() - t0
+    return {"value": round(n / dt, 3), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"whole layer (route, dispatch, expert FFN, combine) on the first {n} of {cfg.T} tokens, "
+                      f"float64 numpy, {dt:.1f} s",
+            "host_cpus": os.cpu_count()}
+
+
+def result_line(cfg, steps, warmup, ms_per_step, ffn_in_ms, calls_ms, counts, cost, R, cpu):
+    tokens_per_s = cfg.T / (ms_per_step * 1e-3)
+    line = {
+        "metric": "MoE-layer tokens/sec (route+dispatch+expert FFN+combine), 1 MI355X",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "f": cfg.f, "E": cfg.E, "k": cfg.k,
+                   "tokens_per_expert_mean": cfg.T * cfg.k / cfg.E, "tokens_per_expert_max": int(counts.max()),
+                   "tokens_per_expert_min": int(counts.min())},
+        "roofline": roofline_entry(cfg, cost, ffn_in_ms, R),
+        "cpu_baseline": cpu,
+        "layer": {"tflops": round(cost.flops / (ms_per_step * 1e-3) / 1e12, 2),
+                  "min_bytes": cost.layer_min_bytes,
+                  "hbm_frac_of_min_bytes": round(cost.layer_min_bytes / (ms_per_step * 1e-3) / R.MI355X_HBM_BYTES_PER_S, 4),
+                  "mfma_frac": round(cost.flops / (ms_per_step * 1e-3) / R.MI355X_BF16_DENSE_FLOPS, 4)
+                  if cfg.dtype == "bf16" else None,
+                  "calls_ms": {k: round(v, 5) for k, v in calls_ms.items()}},
+    }
+    return line
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="mixtral_T256")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--sweep", action="store_true", help="also run the Mixtral-shaped T sweep (one line per T)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=64)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2504_02263_amd import binding as B
+    from paper_2504_02263_amd import roofline as R
+    from workloads import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    if args.workload in synth.CONFIGS:
+        cfg = synth.CONFIGS[args.workload]
+    elif args.workload.startswith("mixtral_T"):
+        cfg = synth.mixtral_sweep_config(int(args.workload[len("mixtral_T"):]))
+    else:
+        raise SystemExit(f"unknown workload {args.workload!r}; known: {sorted(synth.CONFIGS)} and mixtral_T<N>")
+
+    sweep_T = list(synth.MIXTRAL_SWEEP_T) if args.sweep else []
+    T_max = max([cfg.T] + (sweep_T if cfg.name.startswith("mixtral") else []))
+    path = B.MoEPath(T_max, cfg.d, cfg.f, cfg.E, cfg.k, cfg.dtype)
+    W, gen_s = upload_and_pack(cfg, args.seed, path, torch, synth)
+    print(f"[bench] weights generated in {gen_s:.1f} s and packed", file=sys.stderr, flush=True)
+
+    def run(c, want_cpu):
+        x, logits = make_inputs(c, args.seed, synth)
+        x_d, l_d = dev(x, torch), dev(logits, torch)
+        ms, ffn_ms, calls_ms, counts, cost = time_workload(c, path, x_d, l_d, args.steps, args.warmup, torch, R)
+        cpu = None
+        if want_cpu:
+            print("[bench] timing the CPU oracle on a sample ...", file=sys.stderr, flush=True)
+            from oracle import moe_oracle  # the cpu_baseline leg is the only user of the oracle here
+            cpu = cpu_baseline(c, args.seed, W, x, logits, moe_oracle, args.cpu_sample_tokens)
+        return result_line(c, args.steps, args.warmup, ms, ffn_ms, calls_ms, counts, cost, R, cpu)
+
+    if args.sweep and cfg.name.startswith("mixtral"):
+        for T in sweep_T:
+            if T != cfg.T:
+                print(json.dumps(run(cfg.with_T(T), False)), flush=True)
+    print(json.dumps(run(cfg, not args.no_cpu_baseline)), flush=True)
+    path.close()
+
+
+if __name__ == "__main__":
+    main()

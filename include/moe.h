@@ -118,6 +118,18 @@ moe_status moe_expert_ffn(moe_ctx* ctx, int32_t T, const void* xp, const int32_t
                           const void* packed_w, void* h_ws, void* y, void* stream);
 
 /*
+ * The two GEMM stages of moe_expert_ffn as separate calls, named as in Table 3 (same kernels,
+ * same results; moe_expert_ffn is moe_ffn_input followed by moe_ffn_output):
+ *   moe_ffn_input :  h[A, f] = silu(xp * W_gate^T) .* (xp * W_up^T)     reads xp[A, d]
+ *   moe_ffn_output:  y[A, d] = h * W_down^T                              reads h[A, f]
+ * Both take the same packed weight buffer and offsets[E + 1].
+ */
+moe_status moe_ffn_input(moe_ctx* ctx, int32_t T, const void* xp, const int32_t* offsets,
+                         const void* packed_w, void* h, void* stream);
+moe_status moe_ffn_output(moe_ctx* ctx, int32_t T, const void* h, const int32_t* offsets,
+                          const void* packed_w, void* y, void* stream);
+
+/*
  * Combine (Section 2.2: the layer output is the weighted sum of the selected experts' outputs):
  *     out[t, :] = sum_{j = 0..k-1} topk_w[t, j] * y[pos[t, j], :]     (float32 sum, j ascending)
  * In: y[A, d], pos[T, k], topk_w[T, k]. Out: out[T, d] in cfg.dtype.

@@ -23,7 +23,8 @@ MOE_F32, MOE_BF16 = 0, 1
 _DTYPES = {"f32": (MOE_F32, torch.float32), "bf16": (MOE_BF16, torch.bfloat16)}
 
 EXPORTS = ("moe_create", "moe_destroy", "moe_last_error", "moe_status_string", "moe_packed_weight_bytes",
-           "moe_pack_weights", "moe_route", "moe_dispatch", "moe_expert_ffn", "moe_combine")
+           "moe_pack_weights", "moe_route", "moe_dispatch", "moe_expert_ffn", "moe_ffn_input", "moe_ffn_output",
+           "moe_combine")
 
 
 class MoeConfig(ctypes.Structure):
@@ -63,8 +64,11 @@ def load_library() -> ctypes.CDLL:
     lib.moe_route.argtypes = [vp, i32] + [vp] * 5 + [vp]
     lib.moe_dispatch.argtypes = [vp, i32] + [vp] * 6 + [vp]
     lib.moe_expert_ffn.argtypes = [vp, i32] + [vp] * 5 + [vp]
+    lib.moe_ffn_input.argtypes = [vp, i32] + [vp] * 4 + [vp]
+    lib.moe_ffn_output.argtypes = [vp, i32] + [vp] * 4 + [vp]
     lib.moe_combine.argtypes = [vp, i32] + [vp] * 4 + [vp]
-    for name in ("moe_pack_weights", "moe_route", "moe_dispatch", "moe_expert_ffn", "moe_combine"):
+    for name in ("moe_pack_weights", "moe_route", "moe_dispatch", "moe_expert_ffn", "moe_ffn_input", "moe_ffn_output",
+           "moe_combine"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -133,6 +137,14 @@ def moe_expert_ffn(ctx, T, xp, offsets, packed_w, h_ws, y, stream=None) -> None:
                                               _stream(stream)))
 
 
+def moe_ffn_input(ctx, T, xp, offsets, packed_w, h, stream=None) -> None:
+    _check(ctx, load_library().moe_ffn_input(ctx, T, _ptr(xp), _ptr(offsets), _ptr(packed_w), _ptr(h), _stream(stream)))
+
+
+def moe_ffn_output(ctx, T, h, offsets, packed_w, y, stream=None) -> None:
+    _check(ctx, load_library().moe_ffn_output(ctx, T, _ptr(h), _ptr(offsets), _ptr(packed_w), _ptr(y), _stream(stream)))
+
+
 def moe_combine(ctx, T, y, pos, topk_w, out, stream=None) -> None:
     _check(ctx, load_library().moe_combine(ctx, T, _ptr(y), _ptr(pos), _ptr(topk_w), _ptr(out), _stream(stream)))
 
@@ -189,6 +201,12 @@ class MoEPath:
 
     def expert_ffn(self, T, stream=None):
         moe_expert_ffn(self.ctx, T, self.xp, self.offsets, self.packed, self.h, self.y, stream)
+
+    def ffn_input(self, T, stream=None):
+        moe_ffn_input(self.ctx, T, self.xp, self.offsets, self.packed, self.h, stream)
+
+    def ffn_output(self, T, stream=None):
+        moe_ffn_output(self.ctx, T, self.h, self.offsets, self.packed, self.y, stream)
 
     def combine(self, T, stream=None):
         moe_combine(self.ctx, T, self.y, self.pos, self.topk_w, self.out, stream)

@@ -352,31 +352,34 @@ hipError_t launch_pack_weights(const moe_config& cfg, const void* w_gate, const 
   return err;
 }
 
-hipError_t launch_expert_ffn(const moe_config& cfg, int T, const void* xp, const int32_t* offsets, const void* packed,
-                             void* h, void* y, hipStream_t stream) {
+hipError_t launch_ffn_stage(const moe_config& cfg, int stage, int T, const void* in, const int32_t* offsets,
+                            const void* packed, void* out, hipStream_t stream) {
   const int A = T * cfg.k;
   if (A == 0) return hipSuccess;
-  const size_t one = (size_t)cfg.E * cfg.d * cfg.f;
+  const size_t one = (size_t)cfg.E * cfg.d * cfg.f;  // elements of one matrix set
+  const int N = stage == 0 ? cfg.f : cfg.d, K = stage == 0 ? cfg.d : cfg.f;
   if (cfg.dtype == MOE_BF16) {
-    // m-tile height from the mean rows per expert (the host never sees the real counts)
-    // (mean + 3 sqrt(mean) covers the spread of a near-uniform router, so most experts fit one m-tile)
+    // m-tile height from the mean rows per expert (the host never sees the real counts);
+    // mean + 3 sqrt(mean) covers the spread of a near-uniform router, so most experts fit one m-tile
     const float mean = (float)A / cfg.E;
     const float want = mean + 3.f * sqrtf(mean);
     const int MT = want <= 32.f ? 1 : want <= 64.f ? 2 : want <= 128.f ? 4 : 8;
     const uint4* wp = static_cast<const uint4*>(packed);
-    launch_bf16_mt<2>(MT, static_cast<const uint4*>(xp), offsets, wp, static_cast<__bf16*>(h), A, cfg.E, cfg.f, cfg.d,
-                      stream);
-    launch_bf16_mt<1>(MT, static_cast<const uint4*>(h), offsets, wp + 2 * one / 8, static_cast<__bf16*>(y), A, cfg.E,
-                      cfg.d, cfg.f, stream);
+    if (stage == 0)
+      launch_bf16_mt<2>(MT, static_cast<const uint4*>(in), offsets, wp, static_cast<__bf16*>(out), A, cfg.E, N, K, stream);
+    else
+      launch_bf16_mt<1>(MT, static_cast<const uint4*>(in), offsets, wp + 2 * one / 8, static_cast<__bf16*>(out), A,
+                        cfg.E, N, K, stream);
     return hipGetLastError();
   }
   const float* wp = static_cast<const float*>(packed);
-  const int slots = A / 32 + (cfg.E < A ? cfg.E : A);
-  hipLaunchKernelGGL((ffn_f32_kernel<2>), dim3((cfg.f + 63) / 64, slots), dim3(256), 0, stream,
-                     static_cast<const float*>(xp), offsets, wp, wp + one, static_cast<float*>(h), cfg.E, cfg.f, cfg.d);
-  hipLaunchKernelGGL((ffn_f32_kernel<1>), dim3((cfg.d + 63) / 64, slots), dim3(256), 0, stream,
-                     static_cast<const float*>(h), offsets, wp + 2 * one, wp + 2 * one, static_cast<float*>(y), cfg.E,
-                     cfg.d, cfg.f);
+  const dim3 grid((N + 63) / 64, A / 32 + (cfg.E < A ? cfg.E : A));
+  if (stage == 0)
+    hipLaunchKernelGGL((ffn_f32_kernel<2>), grid, dim3(256), 0, stream, static_cast<const float*>(in), offsets, wp,
+                       wp + one, static_cast<float*>(out), cfg.E, N, K);
+  else
+    hipLaunchKernelGGL((ffn_f32_kernel<1>), grid, dim3(256), 0, stream, static_cast<const float*>(in), offsets,
+                       wp + 2 * one, wp + 2 * one, static_cast<float*>(out), cfg.E, N, K);
   return hipGetLastError();
 }
 

@@ -122,13 +122,33 @@ moe_status moe_dispatch(moe_ctx* ctx, int32_t T, const void* x, const int32_t* t
                                      pos, src, static_cast<hipStream_t>(stream)));
 }
 
+moe_status moe_ffn_input(moe_ctx* ctx, int32_t T, const void* xp, const int32_t* offsets, const void* packed_w, void* h,
+                         void* stream) {
+  const void* ptrs[] = {xp, offsets, packed_w, h};
+  const moe_status s = check_call(ctx, "moe_ffn_input", T, ptrs, 4);
+  if (s != MOE_OK) return s;
+  return finish(ctx, "moe_ffn_input",
+                moe::launch_ffn_stage(ctx->cfg, 0, T, xp, offsets, packed_w, h, static_cast<hipStream_t>(stream)));
+}
+
+moe_status moe_ffn_output(moe_ctx* ctx, int32_t T, const void* h, const int32_t* offsets, const void* packed_w, void* y,
+                          void* stream) {
+  const void* ptrs[] = {h, offsets, packed_w, y};
+  const moe_status s = check_call(ctx, "moe_ffn_output", T, ptrs, 4);
+  if (s != MOE_OK) return s;
+  return finish(ctx, "moe_ffn_output",
+                moe::launch_ffn_stage(ctx->cfg, 1, T, h, offsets, packed_w, y, static_cast<hipStream_t>(stream)));
+}
+
 moe_status moe_expert_ffn(moe_ctx* ctx, int32_t T, const void* xp, const int32_t* offsets, const void* packed_w,
                           void* h_ws, void* y, void* stream) {
   const void* ptrs[] = {xp, offsets, packed_w, h_ws, y};
   const moe_status s = check_call(ctx, "moe_expert_ffn", T, ptrs, 5);
   if (s != MOE_OK) return s;
-  return finish(ctx, "moe_expert_ffn",
-                moe::launch_expert_ffn(ctx->cfg, T, xp, offsets, packed_w, h_ws, y, static_cast<hipStream_t>(stream)));
+  hipError_t err = moe::launch_ffn_stage(ctx->cfg, 0, T, xp, offsets, packed_w, h_ws, static_cast<hipStream_t>(stream));
+  if (err == hipSuccess)
+    err = moe::launch_ffn_stage(ctx->cfg, 1, T, h_ws, offsets, packed_w, y, static_cast<hipStream_t>(stream));
+  return finish(ctx, "moe_expert_ffn", err);
 }
 
 moe_status moe_combine(moe_ctx* ctx, int32_t T, const void* y, const int32_t* pos, const float* topk_w, void* out,

@@ -23,8 +23,9 @@ hipError_t launch_combine(const void* y, const int32_t* pos, const float* topk_w
                           int dtype, void* out, hipStream_t stream);
 hipError_t launch_pack_weights(const moe_config& cfg, const void* w_gate, const void* w_up, const void* w_down,
                                void* packed, hipStream_t stream);
-hipError_t launch_expert_ffn(const moe_config& cfg, int T, const void* xp, const int32_t* offsets,
-                             const void* packed, void* h, void* y, hipStream_t stream);
+// stage 0: h = silu(xp Wg^T) .* (xp Wu^T)   (in = xp, out = h);  stage 1: y = h Wd^T   (in = h, out = y)
+hipError_t launch_ffn_stage(const moe_config& cfg, int stage, int T, const void* in, const int32_t* offsets,
+                            const void* packed, void* out, hipStream_t stream);
 size_t packed_weight_bytes(const moe_config& cfg);
 
 }  // namespace moe
