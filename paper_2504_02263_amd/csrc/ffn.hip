@@ -9,6 +9,7 @@
 // weight byte read once per m-tile. Tokens (the other operand) are staged through LDS and shared
 // by the four wavefronts of the workgroup. Per-expert row ranges come from `offsets` on the device.
 #include <math.h>
+#include <stdlib.h>
 #include <type_traits>
 #include "moe_internal.h"
 
@@ -144,7 +145,8 @@ __global__ __launch_bounds__(256) void ffn_bf16_kernel(const u32x4* __restrict__
     constexpr int st = decltype(st_)::value;
     c = min(c, NC - 1);
 #pragma unroll
-    for (int i = 0; i < 4 * NW; ++i) wreg[st][i] = wbase[(size_t)(c * 4 * NW + i) * 64];
+    for (int i = 0; i < 4 * NW; ++i)  // streamed once: non-temporal, so the weights do not evict the tokens from L2
+      wreg[st][i] = __builtin_nontemporal_load(&wbase[(size_t)(c * 4 * NW + i) * 64]);
   };
   const u32x4* xrow[MT];  // this thread's source row in each pass
 #pragma unroll
@@ -180,12 +182,14 @@ __global__ __launch_bounds__(256) void ffn_bf16_kernel(const u32x4* __restrict__
     for (int s = 0; s < 4; ++s) {
 #pragma unroll
       for (int m = 0; m < MT; ++m) {
-        const int row = m * 32 + frow;
-        const bf16x8 b = __builtin_bit_cast(bf16x8, slab[buf][row * 8 + ((2 * s + fg) ^ (row & 7))]);
+        if (m * 32 < rows) {  // uniform over the workgroup: 32-row groups past the segment cost nothing
+          const int row = m * 32 + frow;
+          const bf16x8 b = __builtin_bit_cast(bf16x8, slab[buf][row * 8 + ((2 * s + fg) ^ (row & 7))]);
 #pragma unroll
-        for (int sel = 0; sel < NW; ++sel)
-          acc[sel][m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wreg[st][s * NW + sel]), b,
-                                                                acc[sel][m], 0, 0, 0);
+          for (int sel = 0; sel < NW; ++sel)
+            acc[sel][m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                __builtin_bit_cast(bf16x8, wreg[st][s * NW + sel]), b, acc[sel][m], 0, 0, 0);
+        }
       }
     }
     load_w(st_, c + NST);
@@ -305,8 +309,10 @@ void launch_bf16(const uint4* X, const int32_t* offsets, const uint4* Wp, __bf16
   const int slots = A / BM + (E < A ? E : A);  // upper bound on sum_e ceil(c_e / BM)
   const dim3 grid((N / 32 + 3) / 4, slots), block(256);
   // ring depth: K / 64 chunks must be a multiple of it (K is a multiple of 128)
+  static const char* env_nst = getenv("MOE_DBG_NST");
+  const bool want4 = !(env_nst && atoi(env_nst) == 2);
   if constexpr (MT < 8) {
-    if (K % 256 == 0) {
+    if (K % 256 == 0 && want4) {
     hipLaunchKernelGGL((ffn_bf16_kernel<MT, NW, 4>), grid, block, 0, stream, reinterpret_cast<const u32x4*>(X), offsets,
                        reinterpret_cast<const u32x4*>(Wp), C, E, N, K);
       return;
@@ -363,7 +369,9 @@ hipError_t launch_ffn_stage(const moe_config& cfg, int stage, int T, const void*
     // mean + 3 sqrt(mean) covers the spread of a near-uniform router, so most experts fit one m-tile
     const float mean = (float)A / cfg.E;
     const float want = mean + 3.f * sqrtf(mean);
-    const int MT = want <= 32.f ? 1 : want <= 64.f ? 2 : want <= 128.f ? 4 : 8;
+    int MT = want <= 32.f ? 1 : want <= 64.f ? 2 : want <= 128.f ? 4 : 8;
+    static const char* env_mt = getenv("MOE_DBG_MT");
+    if (env_mt) MT = atoi(env_mt);
     const uint4* wp = static_cast<const uint4*>(packed);
     if (stage == 0)
       launch_bf16_mt<2>(MT, static_cast<const uint4*>(in), offsets, wp, static_cast<__bf16*>(out), A, cfg.E, N, K, stream);

@@ -1,0 +1,106 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+Integer outputs (routing, counts, permutation, copied rows) are checked in full, bit for bit. The
+layer output is checked against the oracle on all tokens when the oracle can afford it (T <= 256)
+and on a seeded sample of tokens beyond that: each token's output depends only on its own row
+and its own k experts, so the oracle computes sampled outputs one by one."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as O
+from paper_2504_02263_amd import binding as B
+from workloads import synth
+
+from test_gpu_parity import dev, host, rel_fro, W_TOL
+
+pytestmark = pytest.mark.gpu
+
+
+class Layer:
+    """One weight set on the GPU (packed once) plus the host copy the oracle reads."""
+
+    def __init__(self, cfg, T_max, seed=0):
+        self.cfg, self.seed = cfg, seed
+        self.W = synth.make_all_expert_weights(cfg, seed, workers=16)
+        self.path = B.MoEPath(T_max, cfg.d, cfg.f, cfg.E, cfg.k, cfg.dtype)
+        wg, wu, wd = (dev(w) for w in self.W)
+        self.path.pack_weights(wg, wu, wd)
+        torch.cuda.synchronize()
+        del wg, wu, wd
+        torch.cuda.empty_cache()
+
+    def weights(self, e):
+        return self.W[0][e], self.W[1][e], self.W[2][e]
+
+    def check(self, cfg, sample=None, x=None, logits=None):
+        """Run the path on cfg's inputs; compare integers in full and `out` on `sample` tokens (None = all)."""
+        T, k = cfg.T, cfg.k
+        x = synth.make_activations(cfg, self.seed) if x is None else x
+        logits = synth.make_logits(cfg, self.seed) if logits is None else logits
+        idx, w, counts, offsets = O.route(logits, k)
+        xp, pos, src = O.dispatch(x, idx, offsets)
+        p = self.path
+        p.out.zero_()
+        p.forward(dev(x), dev(logits))
+        torch.cuda.synchronize()
+        A = T * k
+        assert (host(p.topk_idx)[:T] == idx).all()
+        assert (host(p.counts) == counts).all() and (host(p.offsets) == offsets).all()
+        assert (host(p.pos)[:T] == pos).all() and (host(p.src)[:A] == src).all()
+        assert (host(p.xp)[:A] == xp).all()
+        np.testing.assert_allclose(host(p.topk_w)[:T], w, rtol=0, atol=W_TOL)
+        tokens = list(range(T)) if sample is None else sorted(
+            np.random.default_rng(1234 + T).choice(T, size=min(sample, T), replace=False).tolist())
+        ref = O.token_outputs(x, idx, w, tokens, self.weights)
+        got = host(p.out)[tokens]
+        err = rel_fro(got, ref)
+        # per-token worst case too: no single sampled token may be far off
+        worst = max(rel_fro(got[i:i + 1], ref[i:i + 1]) for i in range(len(tokens)))
+        print(f"{cfg.name}: counts min/mean/max {counts.min()}/{counts.mean():.0f}/{counts.max()}  "
+              f"rel-Frobenius out {err:.2e} over {len(tokens)} tokens (worst token {worst:.2e})")
+        assert np.isfinite(O.widen(host(p.out)[:T])).all()
+        assert err <= 1e-2 and worst <= 2e-2
+        return counts
+
+    def close(self):
+        self.path.close()
+        del self.W
+
+
+@pytest.fixture(scope="module")
+def mixtral():
+    layer = Layer(synth.CONFIGS["mixtral_T256"], T_max=4096)
+    yield layer
+    layer.close()
+
+
+def test_mixtral_T256_all_tokens(mixtral):
+    """The configuration the headline number is quoted on: every output token against the oracle."""
+    mixtral.check(synth.CONFIGS["mixtral_T256"], sample=None)
+
+
+@pytest.mark.parametrize("T", [32, 1024, 4096])
+def test_mixtral_sweep_sampled(mixtral, T):
+    mixtral.check(synth.mixtral_sweep_config(T), sample=48)
+
+
+def test_dbrx_zipf_sampled():
+    cfg = synth.CONFIGS["dbrx_zipf_T1024"]
+    layer = Layer(cfg, T_max=cfg.T)
+    counts = layer.check(cfg, sample=48)
+    assert counts.max() >= 2 * counts.mean()            # the Zipf bias really skews the load
+    layer.close()
+
+
+def test_finegrained_microbatches_sampled():
+    """The many-expert layer as bench.py runs it: 3 micro-batches of 2731/2731/2730 tokens."""
+    cfg = synth.CONFIGS["finegrained_T8192"]
+    x = synth.make_activations(cfg, 0)
+    logits = synth.make_logits(cfg, 0)
+    ranges = synth.microbatch_ranges(cfg.T, cfg.micro_batches)
+    assert [b - a for a, b in ranges] == [2731, 2731, 2730]
+    layer = Layer(cfg, T_max=2731)
+    for a, b in ranges:
+        layer.check(cfg.with_T(b - a), sample=32, x=x[a:b], logits=logits[a:b])
+    layer.close()
