@@ -180,6 +180,9 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="also run the Mixtral-shaped T sweep (one line per T)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=256)
+    ap.add_argument("--calibrate", action="store_true",
+                    help="only run a plain device copy of known size (1 GiB) a few times and print its rate; "
+                         "under rocprofv3 --pmc this gives the scale of the FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -193,6 +196,22 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(2)
+    if args.calibrate:
+        n = 1 << 30
+        src = torch.full((n,), 3, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 10
+        print(json.dumps({"calibration": "device copy", "bytes_read": n, "bytes_written": n, "launches": 13,
+                          "ms": round(dt * 1e3, 4), "GB/s_read_plus_write": round(2 * n / dt / 1e9, 1)}))
+        return
+
     if args.workload in synth.CONFIGS:
         cfg = synth.CONFIGS[args.workload]
     elif args.workload.startswith("mixtral_T"):
