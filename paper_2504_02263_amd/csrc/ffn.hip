@@ -4,12 +4,12 @@
 // bf16 path. Both GEMMs are C[m, n] = sum_k X[m, k] * W[n, k] with K contiguous in X and W. The
 // weights are pre-packed into matrix-core operand order: a "fragment" is the 32 (n) x 16 (k)
 // operand of one v_mfma_f32_32x32x16_bf16, stored as 64 lanes x 16 bytes = 1 KiB where lane
-// l = (n % 32) + 32 * g holds k = 16 * ks + 8 * g .. + 7. A wavefront owns one 32-row n-tile and
-// streams its fragments from HBM straight into registers, 1 KiB fully contiguous per load, each
-// weight byte read once per m-tile. Tokens (the other operand) are staged through LDS and shared
-// by the four wavefronts of the workgroup. Per-expert row ranges come from `offsets` on the device.
+// l = (n % 32) + 32 * g holds k = 16 * ks + 8 * g .. + 7. Fragments come in pairs per k-step:
+// (gate, up) of one 32-column tile for the input GEMM, two neighbouring 32-column tiles for the
+// output GEMM. A wavefront streams its fragments from HBM straight into registers, 1 KiB fully
+// contiguous per load. Tokens (the other operand) are staged through LDS and shared by the
+// wavefronts of the workgroup. Per-expert row ranges come from `offsets` on the device.
 #include <math.h>
-#include <stdlib.h>
 #include <type_traits>
 #include "moe_internal.h"
 
@@ -35,13 +35,17 @@ struct TileLoc {
   int expert;   // -1: this workgroup has no tile
   int row0;     // first row of the m-tile
   int row_end;  // end of the expert's segment
+  int within;   // position inside the expert's block of `per_tile`-sized groups (see locate_tile)
 };
 
-// Map m-tile slot -> (expert, first row). Expert e owns ceil(c_e / BM) consecutive slots in
-// expert order. All 256 threads of the workgroup must call this (thread i handles expert i).
-__device__ __forceinline__ TileLoc locate_tile(const int32_t* __restrict__ offsets, int E, int BM, int slot) {
-  __shared__ int s_wave_total[4];
-  __shared__ int s_loc[3];
+// Work items are ordered expert-major: expert e owns ceil(c_e / BM) * per_tile consecutive
+// positions. Position q inside an expert's block maps to m-tile q % tiles_e and `within`
+// = q / tiles_e, so the m-tiles that share one group of weight columns are neighbours.
+// All threads of the workgroup (>= 256, one per expert) must call this.
+__device__ __forceinline__ TileLoc locate_tile(const int32_t* __restrict__ offsets, int E, int BM, int per_tile,
+                                               int pos) {
+  __shared__ int s_wave_total[8];
+  __shared__ int s_loc[4];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   int lo = 0, hi = 0;
   if (tid < E) {
@@ -55,179 +59,242 @@ __device__ __forceinline__ TileLoc locate_tile(const int32_t* __restrict__ offse
     const int o = __shfl_up(incl, off);
     if (lane >= off) incl += o;
   }
-  if (lane == 63) s_wave_total[w] = incl;
+  if (lane == 63 && w < 8) s_wave_total[w] = incl;
   if (tid == 0) s_loc[0] = -1;
   __syncthreads();
   int excl = incl - nt;
-  for (int ww = 0; ww < w; ++ww) excl += s_wave_total[ww];
-  if (nt > 0 && slot >= excl && slot < excl + nt) {
+  for (int ww = 0; ww < w && ww < 4; ++ww) excl += s_wave_total[ww];  // experts live in the first 4 wavefronts
+  const int first = excl * per_tile;
+  if (nt > 0 && pos >= first && pos < first + nt * per_tile) {
+    const int q = pos - first;
     s_loc[0] = tid;
-    s_loc[1] = lo + (slot - excl) * BM;
+    s_loc[1] = lo + (q % nt) * BM;
     s_loc[2] = hi;
+    s_loc[3] = q / nt;
   }
   __syncthreads();
   TileLoc t;
   t.expert = s_loc[0];
   t.row0 = s_loc[1];
   t.row_end = s_loc[2];
+  t.within = s_loc[3];
   return t;
 }
 
 __device__ __forceinline__ float silu(float g) { return g / (1.f + __expf(-g)); }
 
 // ------------------------------------------------------------------------------------------
-// bf16 weight pre-pack: canonical [E, N, K] (K contiguous) -> fragments
-//   packed[(((e * NT + nt) * KS + ks) * NW + sel) * 64 + lane] (16-byte units),
-//   NT = N / 32, KS = K / 16, NW = matrices interleaved per k-step (2 for gate|up, 1 for down).
+// bf16 weight pre-pack: canonical [E, N, K] matrices (K contiguous) -> fragment pairs
+//   packed[(((e * NP + p) * KS + ks) * 2 + sel) * 64 + lane]   (16-byte units), KS = K / 16.
+// gate_up = true : NP = N / 32, fragment (p, sel) is rows 32 p .. of w0 (gate, sel 0) or w1 (up, sel 1)
+// gate_up = false: NP = N / 64, fragment (p, sel) is rows 32 (2 p + sel) .. of w0
 __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint4* __restrict__ w0, const uint4* __restrict__ w1,
-                                                        int E, int N, int K, int NW, uint4* __restrict__ packed) {
-  const size_t total = (size_t)E * N * (K / 8) * NW;
-  const int NT = N / 32, KS = K / 16;
+                                                        int E, int N, int K, int gate_up,
+                                                        uint4* __restrict__ packed) {
+  const int NP = gate_up ? N / 32 : N / 64, KS = K / 16;
+  const size_t total = (size_t)E * NP * KS * 128;
   for (size_t u = (size_t)blockIdx.x * 256 + threadIdx.x; u < total; u += (size_t)gridDim.x * 256) {
     size_t q = u;
     const int lane = q % 64; q /= 64;
-    const int sel = q % NW;  q /= NW;
+    const int sel = q % 2;   q /= 2;
     const int ks = q % KS;   q /= KS;
-    const int nt = q % NT;   q /= NT;
+    const int p = q % NP;    q /= NP;
     const int e = (int)q;
-    const int n = nt * 32 + (lane & 31);
+    const int n = (gate_up ? p : 2 * p + sel) * 32 + (lane & 31);
     const int kv = ks * 2 + (lane >> 5);  // 16-byte unit along K
-    const uint4* w = sel == 0 ? w0 : w1;
+    const uint4* w = (gate_up && sel) ? w1 : w0;
     packed[u] = w[((size_t)e * N + n) * (K / 8) + kv];
   }
 }
 
 // ------------------------------------------------------------------------------------------
 // bf16 grouped GEMM on the matrix cores.
-//   NW = 2: C = silu(X Wg^T) .* (X Wu^T)  (gate and up fragments interleaved per k-step)
-//   NW = 1: C = X W^T
-// Workgroup = 4 wavefronts; wavefront w owns n-tile nt = 4 * blockIdx.x + w (32 output columns)
-// and all BM = 32 * MT rows of the m-tile. K is walked in chunks of 64 (4 MFMA k-steps).
 //
-// Pipeline. Global loads return in order, so one ring of NST chunks carries both operands:
-// weights for chunk c + NST and the workgroup's share of the token slab for chunk c + NST + 1 are
-// issued in iteration c, into registers. The token share for chunk c + 1 is written to LDS at
-// the end of iteration c (double-buffered slab, one barrier per chunk). At every wait about
-// NST - 1 chunks stay in flight.
+// Workgroup = WN x WM wavefronts. Wavefront (wn, wm) owns weight unit `WN * group + wn` and the
+// 32-row groups [wm * MTW, (wm + 1) * MTW) of an m-tile of BM = 32 * MTW * WM rows.
+//   NW = 2: the unit is a fragment pair; GATEUP: C = silu(X Wg^T) .* (X Wu^T) on one 32-column
+//           tile, applied to the accumulators in registers; otherwise two 32-column tiles of X W^T
+//   NW = 1: the unit is one fragment of a pair (one 32-column tile; loads stride over its twin)
+// K is walked in chunks of 64 (4 MFMA k-steps).
 //
-// LDS slab: [BM rows][8 units of 16 B], unit index XOR (row % 8): the row-major writes and the
-// operand-order reads (32 rows, same logical unit) are both bank-conflict free.
-template <int MT, int NW, int NST>
-__global__ __launch_bounds__(256) void ffn_bf16_kernel(const u32x4* __restrict__ X, const int32_t* __restrict__ offsets,
-                                                       const u32x4* __restrict__ Wp, __bf16* __restrict__ C, int E,
-                                                       int N, int K) {
-  static_assert(NST % 2 == 0, "chunk parity must equal ring-slot parity");
-  constexpr int BM = 32 * MT;
-  __shared__ u32x4 slab[2][BM * 8];
+// Grid (1-D), made for 8 XCDs with one L2 each: workgroups are dealt to XCDs round-robin, so id % 8
+// is the XCD and id / 8 the position in that XCD's queue. Each XCD owns the weight-unit groups
+// g = 8 * j + xcd; its queue is expert-major, then j, then m-tile: the m-tiles of one expert that
+// read the same weights run next to each other on one L2, and no weight line is wanted by two XCDs.
+//
+// Pipeline. Global loads return in order, so one register ring of NST chunks carries both
+// operands: weights for chunk c + NST and the workgroup's share of the token slab for chunk
+// c + NST + 1 are issued in stage c. The token share for chunk c + 1 is written to LDS at the end
+// of stage c (double-buffered slab, one barrier per chunk). Loads never branch (indices past the
+// end are clamped; what they fetch is unused), which keeps the s_waitcnt vmcnt counts exact: about
+// NST - 1 chunks stay in flight across every wait. NTL marks the weight loads non-temporal (for
+// weights that are read once; worth +13 % of streaming bandwidth).
+//
+// LDS slab: [BM rows][8 units of 16 B], unit index XOR ((row >> 1) & 7): both the row-major
+// writes and the operand-order reads (32 rows, same logical unit) are free of bank conflicts
+// (measured with the LDS bank-conflict counter; XOR with row & 7 is not).
+template <int MTW, int NW, int NST, int WN, int WM, bool GATEUP, bool NTL>
+struct Gemm {
+  static constexpr int THREADS = 64 * WN * WM;
+  static constexpr int BM = 32 * MTW * WM;
+  static constexpr int RPP = THREADS / 8;  // slab rows written per pass (8 threads per 128-byte row)
+  static constexpr int PASSES = (BM + RPP - 1) / RPP;
 
-  const TileLoc loc = locate_tile(offsets, E, BM, blockIdx.y);
-  if (loc.expert < 0) return;
+  u32x4 (*slab)[BM * 8];
+  const u32x4* wbase;
+  const u32x4* xrow[PASSES];
+  int NC, swz_w, trow, frow, fg, mbase;
 
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int NT = N / 32, KS = K / 16, NC = K / 64, KV = K / 8;
-  const int nt = blockIdx.x * 4 + w;
-  const bool has_n = nt < NT;
-  const int rows = min(loc.row_end - loc.row0, BM);
-
-  // weights of this wavefront: chunk c, k-step s, matrix sel -> wbase[(c * 4 + s) * NW * 64 + sel * 64]
-  const u32x4* wbase = Wp + ((size_t)loc.expert * NT + (has_n ? nt : 0)) * KS * NW * 64 + lane;
-  // token slab share: per pass p thread loads row p * 32 + tid / 8, unit tid % 8
-  const int trow = tid >> 3, tunit = tid & 7;
-  const int swz_w = trow * 8 + (tunit ^ (trow & 7));  // + p * 256 (rows p*32.. keep row % 8)
-
-  u32x4 wreg[NST][4 * NW];
-  u32x4 treg[NST][MT];
-
-  // Loads never branch: chunk indices past the end are clamped to the last chunk and rows past
-  // the segment to its last row (what they fetch is never used), so the loop body is straight-line
-  // code and the load counter waits stay exact.
-  auto load_w = [&](auto st_, int c) {
-    constexpr int st = decltype(st_)::value;
-    c = min(c, NC - 1);
+  // MU = 32-row groups of this wavefront that hold real rows (the others are skipped entirely)
+  template <int MU>
+  __device__ __forceinline__ void run(floatx16 (&acc)[NW][MTW]) {
+    u32x4 wreg[NST][4 * NW];
+    u32x4 treg[NST][PASSES];
+    auto load_w = [&](auto st_, int c) {
+      constexpr int st = decltype(st_)::value;
+      c = min(c, NC - 1);
 #pragma unroll
-    for (int i = 0; i < 4 * NW; ++i)  // streamed once: non-temporal, so the weights do not evict the tokens from L2
-      wreg[st][i] = __builtin_nontemporal_load(&wbase[(size_t)(c * 4 * NW + i) * 64]);
-  };
-  const u32x4* xrow[MT];  // this thread's source row in each pass
+      for (int s = 0; s < 4; ++s)
 #pragma unroll
-  for (int p = 0; p < MT; ++p) xrow[p] = X + (size_t)(loc.row0 + min(p * 32 + trow, rows - 1)) * KV + tunit;
-  auto load_t = [&](auto st_, int c) {
-    constexpr int st = decltype(st_)::value;
-    c = min(c, NC - 1);
+        for (int i = 0; i < NW; ++i) {
+          const u32x4* p = wbase + (size_t)(c * 4 + s) * 128 + i * 64;
+          wreg[st][s * NW + i] = NTL ? __builtin_nontemporal_load(p) : *p;
+        }
+    };
+    auto load_t = [&](auto st_, int c) {
+      constexpr int st = decltype(st_)::value;
+      c = min(c, NC - 1);
 #pragma unroll
-    for (int p = 0; p < MT; ++p) treg[st][p] = xrow[p][c * 8];
-  };
-  auto store_t = [&](auto st_, auto buf_) {
-    constexpr int st = decltype(st_)::value;
-    constexpr int buf = decltype(buf_)::value;
+      for (int p = 0; p < PASSES; ++p) treg[st][p] = xrow[p][c * 8];
+    };
+    auto store_t = [&](auto st_, auto buf_) {
+      constexpr int st = decltype(st_)::value;
+      constexpr int buf = decltype(buf_)::value;
 #pragma unroll
-    for (int p = 0; p < MT; ++p) slab[buf][p * 256 + swz_w] = treg[st][p];
-  };
-
-  floatx16 acc[NW][MT];
+      for (int p = 0; p < PASSES; ++p)
+        if (BM % RPP == 0 || p * RPP + trow < BM) slab[buf][p * RPP * 8 + swz_w] = treg[st][p];
+    };
+    // One pipeline stage for chunk c held in ring slot st (= c % NST); chunk parity == st parity.
+    auto stage = [&](auto st_, int c) {
+      constexpr int st = decltype(st_)::value;
+      constexpr int buf = st & 1;
+      constexpr int nxt = (st + 1) % NST;
 #pragma unroll
-  for (int s = 0; s < NW; ++s)
+      for (int s = 0; s < 4; ++s) {
 #pragma unroll
-    for (int m = 0; m < MT; ++m)
+        for (int m = 0; m < MU; ++m) {
+          const int row = (mbase + m) * 32 + frow;
+          const bf16x8 b = __builtin_bit_cast(bf16x8, slab[buf][row * 8 + ((2 * s + fg) ^ ((row >> 1) & 7))]);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[s][m][r] = 0.f;
-
-  const int frow = lane & 31, fg = lane >> 5;
-  // One pipeline stage for chunk c held in ring slot st (= c % NST); chunk parity == st parity.
-  auto stage = [&](auto st_, int c) {
-    constexpr int st = decltype(st_)::value;
-    constexpr int buf = st & 1;
-    constexpr int nxt = (st + 1) % NST;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-#pragma unroll
-      for (int m = 0; m < MT; ++m) {
-        if (m * 32 < rows) {  // uniform over the workgroup: 32-row groups past the segment cost nothing
-          const int row = m * 32 + frow;
-          const bf16x8 b = __builtin_bit_cast(bf16x8, slab[buf][row * 8 + ((2 * s + fg) ^ (row & 7))]);
-#pragma unroll
-          for (int sel = 0; sel < NW; ++sel)
-            acc[sel][m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                __builtin_bit_cast(bf16x8, wreg[st][s * NW + sel]), b, acc[sel][m], 0, 0, 0);
+          for (int i = 0; i < NW; ++i)
+            acc[i][m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wreg[st][s * NW + i]), b,
+                                                                acc[i][m], 0, 0, 0);
         }
       }
-    }
-    load_w(st_, c + NST);
-    store_t(std::integral_constant<int, nxt>{}, std::integral_constant<int, buf ^ 1>{});
-    load_t(std::integral_constant<int, nxt>{}, c + 1 + NST);
+      load_w(st_, c + NST);
+      store_t(std::integral_constant<int, nxt>{}, std::integral_constant<int, buf ^ 1>{});
+      load_t(std::integral_constant<int, nxt>{}, c + 1 + NST);
+      __syncthreads();
+    };
+
+    // prologue: chunk 0 tokens straight to LDS; then the steady-state issue order W[c], tokens[c + 1]
+    load_t(std::integral_constant<int, 0>{}, 0);
+    store_t(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    static_for<0, NST>([&](auto st_) {
+      constexpr int st = decltype(st_)::value;
+      load_w(st_, st);
+      load_t(std::integral_constant<int, (st + 1) % NST>{}, st + 1);
+    });
     __syncthreads();
-  };
+    // NC is a multiple of NST (K is a multiple of 128 and NST is 2), so there is no remainder loop
+    for (int c0 = 0; c0 < NC; c0 += NST) static_for<0, NST>([&](auto st_) { stage(st_, c0 + decltype(st_)::value); });
+  }
+};
 
-  // prologue: chunk 0 tokens straight to LDS; then the steady-state issue order W[c], tokens[c + 1]
-  load_t(std::integral_constant<int, 0>{}, 0);
-  store_t(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
-  static_for<0, NST>([&](auto st_) {
-    constexpr int st = decltype(st_)::value;
-    load_w(st_, st);
-    load_t(std::integral_constant<int, (st + 1) % NST>{}, st + 1);
+template <int MTW, int NW, int NST, int WN, int WM, bool GATEUP, bool NTL>
+__global__ __launch_bounds__(64 * WN * WM) void ffn_bf16_kernel(const u32x4* __restrict__ X,
+                                                               const int32_t* __restrict__ offsets,
+                                                               const u32x4* __restrict__ Wp, __bf16* __restrict__ C,
+                                                               int E, int N, int K) {
+  static_assert(NST % 2 == 0, "chunk parity must equal ring-slot parity");
+  static_assert(WN * WM >= 4, "the tile locator needs one thread per expert (256)");
+  static_assert(NW == 2 || !GATEUP, "gate and up fragments are consumed together");
+  using G = Gemm<MTW, NW, NST, WN, WM, GATEUP, NTL>;
+  constexpr int BM = G::BM;
+  __shared__ u32x4 slab[2][BM * 8];
+
+  const int NP = GATEUP ? N / 32 : N / 64;            // fragment pairs along N
+  const int units = NW == 2 ? NP : 2 * NP;            // weight units (one per wavefront column)
+  const int groups = (units + WN - 1) / WN;
+  const int groups_per_xcd = (groups + 7) / 8;
+  const int xcd = blockIdx.x & 7;
+  const TileLoc loc = locate_tile(offsets, E, BM, groups_per_xcd, blockIdx.x >> 3);
+  if (loc.expert < 0) return;
+  const int group = loc.within * 8 + xcd;
+  if (group >= groups) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int wn = w % WN, wm = w / WN;
+  const int KS = K / 16, KV = K / 8;
+  const int unit = group * WN + wn;
+  const bool has_n = unit < units;
+  const int rows = min(loc.row_end - loc.row0, BM);
+
+  G g;
+  g.slab = slab;
+  g.NC = K / 64;
+  {
+    const int u = has_n ? unit : 0;
+    const int pair = NW == 2 ? u : u >> 1, sel = NW == 2 ? 0 : u & 1;
+    g.wbase = Wp + ((size_t)loc.expert * NP + pair) * KS * 128 + sel * 64 + lane;
+  }
+  g.trow = tid >> 3;
+  const int tunit = tid & 7;
+  g.swz_w = g.trow * 8 + (tunit ^ ((g.trow >> 1) & 7));
+#pragma unroll
+  for (int p = 0; p < G::PASSES; ++p)
+    g.xrow[p] = X + (size_t)(loc.row0 + min(p * G::RPP + g.trow, rows - 1)) * KV + tunit;
+  g.frow = lane & 31;
+  g.fg = lane >> 5;
+  g.mbase = wm * MTW;
+
+  floatx16 acc[NW][MTW];
+#pragma unroll
+  for (int i = 0; i < NW; ++i)
+#pragma unroll
+    for (int m = 0; m < MTW; ++m)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][m][r] = 0.f;
+
+  // 32-row groups of this wavefront that hold real rows; every wavefront runs the same number of
+  // stages and barriers whatever its count is.
+  int mu = (rows - g.mbase * 32 + 31) / 32;
+  mu = __builtin_amdgcn_readfirstlane(max(0, min(mu, MTW)));
+  static_for<0, MTW + 1>([&](auto mu_) {
+    if (mu == decltype(mu_)::value) g.template run<decltype(mu_)::value>(acc);
   });
-  __syncthreads();
-
-  // NC is a multiple of NST (the launcher picks NST so), so there is no remainder loop
-  for (int c0 = 0; c0 < NC; c0 += NST) static_for<0, NST>([&](auto st_) { stage(st_, c0 + decltype(st_)::value); });
 
   if (!has_n) return;
-  // acc[..][m][r] holds C[row = m * 32 + lane % 32][col = nt * 32 + 8 * (r / 4) + 4 * (lane / 32) + r % 4]
+  // acc[i][m][r] holds row (mbase + m) * 32 + lane % 32, column 8 * (r / 4) + 4 * (lane / 32) + r % 4 of its tile
 #pragma unroll
-  for (int m = 0; m < MT; ++m) {
-    const int row = m * 32 + frow;
+  for (int m = 0; m < MTW; ++m) {
+    const int row = (g.mbase + m) * 32 + g.frow;
     if (row < rows) {
-      __bf16* crow = C + (size_t)(loc.row0 + row) * N + nt * 32 + 4 * fg;
+      __bf16* crow = C + (size_t)(loc.row0 + row) * N + 4 * g.fg;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        bf16x4 o;
+      for (int i = 0; i < (GATEUP ? 1 : NW); ++i) {
+        const int tile = GATEUP ? unit : (NW == 2 ? 2 * unit + i : unit);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          float v = acc[0][m][q * 4 + i];
-          if (NW == 2) v = silu(v) * acc[NW - 1][m][q * 4 + i];
-          o[i] = (__bf16)v;
+        for (int q = 0; q < 4; ++q) {
+          bf16x4 o;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            float v = acc[i][m][q * 4 + j];
+            if (GATEUP) v = silu(v) * acc[NW - 1][m][q * 4 + j];
+            o[j] = (__bf16)v;
+          }
+          *reinterpret_cast<bf16x4*>(crow + tile * 32 + 8 * q) = o;
         }
-        *reinterpret_cast<bf16x4*>(crow + 8 * q) = o;
       }
     }
   }
@@ -244,7 +311,7 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ 
   __shared__ float xs[BM][BK + 1];
   __shared__ float ws[NW][BN][BK + 1];
 
-  const TileLoc loc = locate_tile(offsets, E, BM, blockIdx.y);
+  const TileLoc loc = locate_tile(offsets, E, BM, 1, blockIdx.y);
   if (loc.expert < 0) return;
   const int tid = threadIdx.x, tx = tid & 63, ty = tid >> 6;
   const int rows = min(loc.row_end - loc.row0, BM);
@@ -302,35 +369,21 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ 
   }
 }
 
-template <int MT, int NW>
-void launch_bf16(const uint4* X, const int32_t* offsets, const uint4* Wp, __bf16* C, int A, int E, int N, int K,
-                 hipStream_t stream) {
-  constexpr int BM = 32 * MT;
-  const int slots = A / BM + (E < A ? E : A);  // upper bound on sum_e ceil(c_e / BM)
-  const dim3 grid((N / 32 + 3) / 4, slots), block(256);
-  // ring depth: K / 64 chunks must be a multiple of it (K is a multiple of 128)
-  static const char* env_nst = getenv("MOE_DBG_NST");
-  const bool want4 = !(env_nst && atoi(env_nst) == 2);
-  if constexpr (MT < 8) {
-    if (K % 256 == 0 && want4) {
-    hipLaunchKernelGGL((ffn_bf16_kernel<MT, NW, 4>), grid, block, 0, stream, reinterpret_cast<const u32x4*>(X), offsets,
-                       reinterpret_cast<const u32x4*>(Wp), C, E, N, K);
-      return;
-    }
-  }
-    hipLaunchKernelGGL((ffn_bf16_kernel<MT, NW, 2>), grid, block, 0, stream, reinterpret_cast<const u32x4*>(X), offsets,
-                       reinterpret_cast<const u32x4*>(Wp), C, E, N, K);
-}
+// Upper bound on the m-tiles of all experts: sum_e ceil(c_e / BM) <= A / BM + min(E, A).
+inline int max_m_tiles(int A, int E, int BM) { return A / BM + (E < A ? E : A); }
 
-template <int NW>
-void launch_bf16_mt(int MT, const uint4* X, const int32_t* offsets, const uint4* Wp, __bf16* C, int A, int E, int N,
-                    int K, hipStream_t stream) {
-  switch (MT) {
-    case 1: launch_bf16<1, NW>(X, offsets, Wp, C, A, E, N, K, stream); break;
-    case 2: launch_bf16<2, NW>(X, offsets, Wp, C, A, E, N, K, stream); break;
-    case 4: launch_bf16<4, NW>(X, offsets, Wp, C, A, E, N, K, stream); break;
-    default: launch_bf16<8, NW>(X, offsets, Wp, C, A, E, N, K, stream); break;
-  }
+template <int MTW, int NW, int NST, int WN, int WM, bool GATEUP, bool NTL>
+void launch_bf16(const void* X, const int32_t* offsets, const void* Wp, void* C, int A, int E, int N, int K,
+                 hipStream_t stream) {
+  constexpr int BM = 32 * MTW * WM;
+  const int NP = GATEUP ? N / 32 : N / 64;
+  const int units = NW == 2 ? NP : 2 * NP;
+  const int groups = (units + WN - 1) / WN;
+  const int groups_per_xcd = (groups + 7) / 8;
+  const dim3 grid(8 * groups_per_xcd * max_m_tiles(A, E, BM)), block(64 * WN * WM);
+  hipLaunchKernelGGL((ffn_bf16_kernel<MTW, NW, NST, WN, WM, GATEUP, NTL>), grid, block, 0, stream,
+                     static_cast<const u32x4*>(X), offsets, static_cast<const u32x4*>(Wp), static_cast<__bf16*>(C), E,
+                     N, K);
 }
 
 }  // namespace
@@ -346,9 +399,9 @@ hipError_t launch_pack_weights(const moe_config& cfg, const void* w_gate, const 
   if (cfg.dtype == MOE_BF16) {
     uint4* p = static_cast<uint4*>(packed);
     hipLaunchKernelGGL(pack_bf16_kernel, dim3(4096), dim3(256), 0, stream, static_cast<const uint4*>(w_gate),
-                       static_cast<const uint4*>(w_up), cfg.E, cfg.f, cfg.d, 2, p);
+                       static_cast<const uint4*>(w_up), cfg.E, cfg.f, cfg.d, 1, p);
     hipLaunchKernelGGL(pack_bf16_kernel, dim3(4096), dim3(256), 0, stream, static_cast<const uint4*>(w_down),
-                       static_cast<const uint4*>(w_down), cfg.E, cfg.d, cfg.f, 1, p + 2 * one / 8);
+                       static_cast<const uint4*>(w_down), cfg.E, cfg.d, cfg.f, 0, p + 2 * one / 8);
     return hipGetLastError();
   }
   float* p = static_cast<float*>(packed);
@@ -365,23 +418,28 @@ hipError_t launch_ffn_stage(const moe_config& cfg, int stage, int T, const void*
   const size_t one = (size_t)cfg.E * cfg.d * cfg.f;  // elements of one matrix set
   const int N = stage == 0 ? cfg.f : cfg.d, K = stage == 0 ? cfg.d : cfg.f;
   if (cfg.dtype == MOE_BF16) {
-    // m-tile height from the mean rows per expert (the host never sees the real counts);
-    // mean + 3 sqrt(mean) covers the spread of a near-uniform router, so most experts fit one m-tile
+    // The host never sees the per-expert counts, so the tile shape comes from the mean rows per
+    // expert: mean + 3 sqrt(mean) covers the spread of a near-uniform router, so most experts fit
+    // one m-tile. Up to 128 rows: 8 wavefronts side by side along N, weights streamed once
+    // (non-temporal). Above: 4 x 2 wavefronts on 256-row tiles, weights shared through L2.
     const float mean = (float)A / cfg.E;
     const float want = mean + 3.f * sqrtf(mean);
-    int MT = want <= 32.f ? 1 : want <= 64.f ? 2 : want <= 128.f ? 4 : 8;
-    static const char* env_mt = getenv("MOE_DBG_MT");
-    if (env_mt) MT = atoi(env_mt);
-    const uint4* wp = static_cast<const uint4*>(packed);
-    if (stage == 0)
-      launch_bf16_mt<2>(MT, static_cast<const uint4*>(in), offsets, wp, static_cast<__bf16*>(out), A, cfg.E, N, K, stream);
-    else
-      launch_bf16_mt<1>(MT, static_cast<const uint4*>(in), offsets, wp + 2 * one / 8, static_cast<__bf16*>(out), A,
-                        cfg.E, N, K, stream);
+    const char* w = static_cast<const char*>(packed) + (stage == 0 ? 0 : 2 * one * 2);
+    if (stage == 0) {
+      if (want <= 32.f) launch_bf16<1, 2, 2, 8, 1, true, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
+      else if (want <= 64.f) launch_bf16<2, 2, 2, 8, 1, true, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
+      else if (want <= 128.f) launch_bf16<4, 2, 2, 8, 1, true, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
+      else launch_bf16<4, 2, 2, 4, 2, true, false>(in, offsets, w, out, A, cfg.E, N, K, stream);
+    } else {
+      if (want <= 32.f) launch_bf16<1, 1, 2, 8, 1, false, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
+      else if (want <= 64.f) launch_bf16<2, 1, 2, 8, 1, false, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
+      else if (want <= 128.f) launch_bf16<4, 1, 2, 8, 1, false, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
+      else launch_bf16<4, 2, 2, 4, 2, false, false>(in, offsets, w, out, A, cfg.E, N, K, stream);
+    }
     return hipGetLastError();
   }
   const float* wp = static_cast<const float*>(packed);
-  const dim3 grid((N + 63) / 64, A / 32 + (cfg.E < A ? cfg.E : A));
+  const dim3 grid((N + 63) / 64, max_m_tiles(A, cfg.E, 32));
   if (stage == 0)
     hipLaunchKernelGGL((ffn_f32_kernel<2>), grid, dim3(256), 0, stream, static_cast<const float*>(in), offsets, wp,
                        wp + one, static_cast<float*>(out), cfg.E, N, K);
