@@ -301,6 +301,181 @@ __global__ __launch_bounds__(64 * WN * WM) void ffn_bf16_kernel(const u32x4* __r
 }
 
 // ------------------------------------------------------------------------------------------
+// bf16 grouped GEMM for large per-expert batches (matrix-core bound).
+//
+// Workgroup = 4 wavefronts, one per SIMD with the whole 512-entry register file: wavefront w owns
+// fragment pair `4 * group + w` and all 256 rows of the m-tile (2 x 8 accumulator tiles = 256
+// registers). Same grid order and weight layout as above; weights come with ordinary (cached)
+// loads because the m-tiles of an expert share them through L2.
+//
+// With one wavefront per SIMD nothing hides LDS latency but the wavefront's own schedule, so the
+// k-step loop is software-pipelined by hand: the 8 token fragments of k-step s + 1 are read while
+// the 16 MFMAs of k-step s issue (one ds_read per two MFMAs), which the compiler would otherwise
+// undo; a scheduling barrier at every k-step boundary plus per-k-step group barriers pin that
+// order. The slab is triple-buffered: stage c reads buffer c % 3, reads the first fragments of
+// chunk c + 1 from buffer (c + 1) % 3 before the stage's barrier, and writes the tokens of chunk
+// c + 2 into buffer (c + 2) % 3, so no MFMA waits on LDS right after a barrier.
+// MU (2, 4, 6 or 8) = 32-row groups that hold real rows, rounded up to even; the rest are skipped.
+template <bool GATEUP, int MU, int NST>
+__device__ __forceinline__ void wide_tile(const u32x4* __restrict__ X, const u32x4* __restrict__ wbase,
+                                          __bf16* __restrict__ C, u32x4* __restrict__ slab, int row0, int rows, int N,
+                                          int K, int pair, bool has_n) {
+  constexpr int BM = 256, BUF = BM * 8;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int NC = K / 64, KV = K / 8;
+  const int trow = tid >> 3, tunit = tid & 7;
+  const int swz_w = trow * 8 + (tunit ^ ((trow >> 1) & 7));
+  const u32x4* xrow[MU];  // pass p covers rows 32 p .. 32 p + 31
+#pragma unroll
+  for (int p = 0; p < MU; ++p) xrow[p] = X + (size_t)(row0 + min(p * 32 + trow, rows - 1)) * KV + tunit;
+  const int frow = lane & 31, fg = lane >> 5;
+  int rd[4];  // slab unit of this lane's fragment piece in k-step s (row group 0)
+#pragma unroll
+  for (int s = 0; s < 4; ++s) rd[s] = frow * 8 + ((2 * s + fg) ^ ((frow >> 1) & 7));
+
+  u32x4 wreg[NST][8];
+  u32x4 treg[MU];
+  bf16x8 bfr[2][MU];
+  floatx16 acc[2][MU];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int m = 0; m < MU; ++m)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][m][r] = 0.f;
+
+  auto load_t = [&](int c) {
+    c = min(c, NC - 1);
+#pragma unroll
+    for (int p = 0; p < MU; ++p) treg[p] = xrow[p][c * 8];
+  };
+  auto store_t = [&](int boff) {
+#pragma unroll
+    for (int p = 0; p < MU; ++p) slab[boff + p * 256 + swz_w] = treg[p];
+  };
+  auto load_w_step = [&](auto st_, int c, int s) {
+    constexpr int st = decltype(st_)::value;
+    c = min(c, NC - 1);
+    wreg[st][2 * s] = wbase[(size_t)(c * 4 + s) * 128];
+    wreg[st][2 * s + 1] = wbase[(size_t)(c * 4 + s) * 128 + 64];
+  };
+
+  // prologue: chunks 0 and 1 to LDS, chunk 2 in flight, weights of chunks 0 and 1 in flight
+  load_t(0);
+  store_t(0);
+  load_t(1);
+  store_t(BUF);
+  load_t(2);
+  static_for<0, NST>([&](auto st_) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) load_w_step(st_, decltype(st_)::value, s);
+  });
+  __syncthreads();
+#pragma unroll
+  for (int m = 0; m < MU; ++m) bfr[0][m] = __builtin_bit_cast(bf16x8, slab[m * 256 + rd[0]]);
+
+  int cur = 0, nxt = BUF, wr = 2 * BUF;
+  auto stage = [&](auto st_, int c) {
+    constexpr int st = decltype(st_)::value;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+#pragma unroll
+      for (int m = 0; m < MU; ++m) {
+        if (s < 3) bfr[(s + 1) & 1][m] = __builtin_bit_cast(bf16x8, slab[cur + m * 256 + rd[s + 1]]);
+        else bfr[0][m] = __builtin_bit_cast(bf16x8, slab[nxt + m * 256 + rd[0]]);
+        acc[0][m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wreg[st][2 * s]),
+                                                            bfr[s & 1][m], acc[0][m], 0, 0, 0);
+        acc[1][m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wreg[st][2 * s + 1]),
+                                                            bfr[s & 1][m], acc[1][m], 0, 0, 0);
+      }
+      if (s == 0) {
+        // token loads go out before this stage's weight loads: loads return in order, and waiting
+        // for these tokens one stage from now must not wait for weights needed NST stages from now
+        store_t(wr);      // tokens of chunk c + 2
+        load_t(c + 3);
+      }
+      load_w_step(st_, c + NST, s);  // this k-step's weight registers are free again
+#pragma unroll
+      for (int m = 0; m < MU; ++m) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 LDS read
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // 2 MFMA
+        if (s == 0) {
+          __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // 1 LDS write
+          __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // 1 global load
+        }
+      }
+      __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);  // the two weight loads
+      __builtin_amdgcn_sched_barrier(0);                  // nothing moves across a k-step boundary
+    }
+    __syncthreads();
+    const int t = cur;
+    cur = nxt;
+    nxt = wr;
+    wr = t;
+  };
+  for (int c0 = 0; c0 < NC; c0 += NST) static_for<0, NST>([&](auto st_) { stage(st_, c0 + decltype(st_)::value); });
+
+  if (!has_n) return;
+#pragma unroll
+  for (int m = 0; m < MU; ++m) {
+    const int row = m * 32 + frow;
+    if (row < rows) {
+      __bf16* crow = C + (size_t)(row0 + row) * N + 4 * fg;
+#pragma unroll
+      for (int i = 0; i < (GATEUP ? 1 : 2); ++i) {
+        const int tile = GATEUP ? pair : 2 * pair + i;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          bf16x4 o;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            float v = acc[i][m][q * 4 + j];
+            if (GATEUP) v = silu(v) * acc[1][m][q * 4 + j];
+            o[j] = (__bf16)v;
+          }
+          *reinterpret_cast<bf16x4*>(crow + tile * 32 + 8 * q) = o;
+        }
+      }
+    }
+  }
+}
+
+template <bool GATEUP>
+__global__ __launch_bounds__(256) void ffn_bf16_wide_kernel(const u32x4* __restrict__ X,
+                                                           const int32_t* __restrict__ offsets,
+                                                           const u32x4* __restrict__ Wp, __bf16* __restrict__ C, int E,
+                                                           int N, int K) {
+  constexpr int BM = 256;
+  __shared__ u32x4 slab[3 * BM * 8];
+  const int NP = GATEUP ? N / 32 : N / 64;
+  const int groups = (NP + 3) / 4;
+  const int groups_per_xcd = (groups + 7) / 8;
+  const int xcd = blockIdx.x & 7;
+  const TileLoc loc = locate_tile(offsets, E, BM, groups_per_xcd, blockIdx.x >> 3);
+  if (loc.expert < 0) return;
+  const int group = loc.within * 8 + xcd;
+  if (group >= groups) return;
+  const int pair = group * 4 + (threadIdx.x >> 6);
+  const bool has_n = pair < NP;
+  const int rows = min(loc.row_end - loc.row0, BM);
+  const u32x4* wbase = Wp + ((size_t)loc.expert * NP + (has_n ? pair : 0)) * (K / 16) * 128 + (threadIdx.x & 63);
+  const int mu = __builtin_amdgcn_readfirstlane((rows + 63) / 64);  // pairs of 32-row groups
+  // small tiles have registers to spare: a deeper weight ring keeps them streaming (K / 64 must divide by it)
+  const bool deep = (K % 256) == 0;
+  if (mu == 1) {
+    if (deep) wide_tile<GATEUP, 2, 4>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
+    else wide_tile<GATEUP, 2, 2>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
+  } else if (mu == 2) {
+    if (deep) wide_tile<GATEUP, 4, 4>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
+    else wide_tile<GATEUP, 4, 2>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
+  } else if (mu == 3) {
+    wide_tile<GATEUP, 6, 2>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
+  } else {
+    wide_tile<GATEUP, 8, 2>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
 // f32 grouped GEMM, plain FMA: 32 (m) x 64 (n) tile per workgroup, K in chunks of 32 through LDS.
 // Thread (tx = tid % 64, ty = tid / 64) computes rows ty * 8 .. + 7 of column tx.
 template <int NW>
@@ -386,6 +561,16 @@ void launch_bf16(const void* X, const int32_t* offsets, const void* Wp, void* C,
                      N, K);
 }
 
+template <bool GATEUP>
+void launch_bf16_wide(const void* X, const int32_t* offsets, const void* Wp, void* C, int A, int E, int N, int K,
+                      hipStream_t stream) {
+  const int NP = GATEUP ? N / 32 : N / 64;
+  const int groups_per_xcd = ((NP + 3) / 4 + 7) / 8;
+  const dim3 grid(8 * groups_per_xcd * max_m_tiles(A, E, 256)), block(256);
+  hipLaunchKernelGGL((ffn_bf16_wide_kernel<GATEUP>), grid, block, 0, stream, static_cast<const u32x4*>(X), offsets,
+                     static_cast<const u32x4*>(Wp), static_cast<__bf16*>(C), E, N, K);
+}
+
 }  // namespace
 
 size_t packed_weight_bytes(const moe_config& cfg) {
@@ -421,7 +606,7 @@ hipError_t launch_ffn_stage(const moe_config& cfg, int stage, int T, const void*
     // The host never sees the per-expert counts, so the tile shape comes from the mean rows per
     // expert: mean + 3 sqrt(mean) covers the spread of a near-uniform router, so most experts fit
     // one m-tile. Up to 128 rows: 8 wavefronts side by side along N, weights streamed once
-    // (non-temporal). Above: 4 x 2 wavefronts on 256-row tiles, weights shared through L2.
+    // (non-temporal). Above: the 256-row matrix-core-bound kernel, weights shared through L2.
     const float mean = (float)A / cfg.E;
     const float want = mean + 3.f * sqrtf(mean);
     const char* w = static_cast<const char*>(packed) + (stage == 0 ? 0 : 2 * one * 2);
@@ -429,12 +614,12 @@ hipError_t launch_ffn_stage(const moe_config& cfg, int stage, int T, const void*
       if (want <= 32.f) launch_bf16<1, 2, 2, 8, 1, true, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
       else if (want <= 64.f) launch_bf16<2, 2, 2, 8, 1, true, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
       else if (want <= 128.f) launch_bf16<4, 2, 2, 8, 1, true, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
-      else launch_bf16<4, 2, 2, 4, 2, true, false>(in, offsets, w, out, A, cfg.E, N, K, stream);
+      else launch_bf16_wide<true>(in, offsets, w, out, A, cfg.E, N, K, stream);
     } else {
       if (want <= 32.f) launch_bf16<1, 1, 2, 8, 1, false, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
       else if (want <= 64.f) launch_bf16<2, 1, 2, 8, 1, false, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
       else if (want <= 128.f) launch_bf16<4, 1, 2, 8, 1, false, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
-      else launch_bf16<4, 2, 2, 4, 2, false, false>(in, offsets, w, out, A, cfg.E, N, K, stream);
+      else launch_bf16_wide<false>(in, offsets, w, out, A, cfg.E, N, K, stream);
     }
     return hipGetLastError();
   }

@@ -137,6 +137,8 @@ FFN_CASES = [
     (40, 256, 512, 8, 2, "bf16"), (160, 256, 512, 8, 2, "bf16"), (320, 256, 512, 8, 2, "bf16"),
     (800, 256, 512, 8, 2, "bf16"), (700, 384, 640, 4, 2, "bf16"), (100, 384, 128, 16, 4, "bf16"),
     (333, 128, 384, 64, 6, "bf16"), (64, 256, 512, 8, 2, "f32"), (300, 128, 384, 5, 3, "f32"),
+    # large-batch kernel: shortest possible K loop (2 chunks), ragged multi-tile segments, one 32-row group
+    (600, 128, 128, 2, 1, "bf16"), (1100, 256, 384, 3, 2, "bf16"), (150, 128, 256, 1, 1, "bf16"),
 ]
 
 
