@@ -53,37 +53,67 @@ def make_inputs(cfg, seed, synth):
     return synth.make_activations(cfg, seed), synth.make_logits(cfg, seed)
 
 
-def time_workload(cfg, path, x_d, logits_d, steps, warmup, torch, R):
-    """W warm-up steps, then exactly K timed steps between device synchronisations."""
-    T = cfg.T
-    stream = torch.cuda.current_stream()
+def time_workload(cfg, paths, x_d, logits_d, steps, warmup, torch, R, synth):
+    """W warm-up steps, then exactly K timed steps between device synchronisations.
 
-    def step(ev=None):
-        path.route(logits_d, T, stream)
-        path.dispatch(x_d, T, stream)
-        if ev is not None:
-            ev[0].record(stream)
-        path.ffn_input(T, stream)
-        if ev is not None:
-            ev[1].record(stream)
-        path.ffn_output(T, stream)
-        path.combine(T, stream)
+    A step runs the whole path over the batch. With cfg.micro_batches = m > 1 the batch is cut
+    into m contiguous micro-batches issued on two alternating streams (each stream has its own
+    buffer set; the packed weights are shared), the single-GPU echo of the paper's ping-pong
+    micro-batching (Section 4.1)."""
+    ranges = synth.microbatch_ranges(cfg.T, cfg.micro_batches)
+    if cfg.micro_batches > 1:
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    else:
+        streams = [torch.cuda.current_stream()]
+
+    def step(ev=None, serial=False):
+        for i, (a, b) in enumerate(ranges):
+            j = 0 if serial else i % len(streams)
+            path, stream = paths[j], streams[j]
+            T = b - a
+            path.route(logits_d[a:b], T, stream)
+            path.dispatch(x_d[a:b], T, stream)
+            if ev is not None:
+                ev[i][0].record(stream)
+            path.ffn_input(T, stream)
+            if ev is not None:
+                ev[i][1].record(stream)
+            path.ffn_output(T, stream)
+            path.combine(T, stream)
+
+    def sync():
+        torch.cuda.synchronize()
 
     for _ in range(warmup):
         step()
-    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
-    torch.cuda.synchronize()
+    m = len(ranges)
+    events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(m)]
+              for _ in range(steps)]
+    sync()
     t0 = time.perf_counter()
     for i in range(steps):
         step(events[i])
-    torch.cuda.synchronize()
+    sync()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / steps
-    ffn_in_ms = float(np.mean([a.elapsed_time(b) for a, b in events]))
+    ffn_in_ms = float(np.mean([a.elapsed_time(b) for evs in events for a, b in evs]))
 
-    # per-call breakdown (separate, untimed pass)
+    serial_ms = None
+    if m > 1:   # the same micro-batches back to back on one stream, for comparison
+        for _ in range(2):
+            step(serial=True)
+        sync()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step(serial=True)
+        sync()
+        serial_ms = (time.perf_counter() - t0) * 1e3 / steps
+
+    # per-call breakdown on the first micro-batch (separate, untimed pass)
+    a, b = ranges[0]
+    T, path, stream = b - a, paths[0], streams[0]
     names = ["route", "dispatch", "ffn_input", "ffn_output", "combine"]
-    calls = [lambda: path.route(logits_d, T, stream), lambda: path.dispatch(x_d, T, stream),
+    calls = [lambda: path.route(logits_d[a:b], T, stream), lambda: path.dispatch(x_d[a:b], T, stream),
              lambda: path.ffn_input(T, stream), lambda: path.ffn_output(T, stream), lambda: path.combine(T, stream)]
     reps = max(5, min(steps, 20))
     acc = {n: [] for n in names}
@@ -93,16 +123,21 @@ def time_workload(cfg, path, x_d, logits_d, steps, warmup, torch, R):
         for i, c in enumerate(calls):
             c()
             evs[i + 1].record(stream)
-        torch.cuda.synchronize()
+        sync()
         for i, n in enumerate(names):
             acc[n].append(evs[i].elapsed_time(evs[i + 1]))
     calls_ms = {n: float(np.median(v)) for n, v in acc.items()}
 
-    counts = path.counts.cpu().numpy()
+    counts = path.counts.cpu().numpy()          # of the first micro-batch
     active = int((counts > 0).sum())
     s = 2 if cfg.dtype == "bf16" else 4
-    cost = R.layer_cost(T, cfg.d, cfg.f, cfg.E, cfg.k, s, active_experts=active)
-    return ms_per_step, ffn_in_ms, calls_ms, counts, cost
+    # cost of one launch of the dominant kernel (one micro-batch) and of the whole step
+    launch_cost = R.layer_cost(T, cfg.d, cfg.f, cfg.E, cfg.k, s, active_experts=active)
+    step_flops = sum(R.layer_cost(q - p, cfg.d, cfg.f, cfg.E, cfg.k, s, active_experts=active).flops for p, q in ranges)
+    step_min_bytes = sum(R.layer_cost(q - p, cfg.d, cfg.f, cfg.E, cfg.k, s, active_experts=active).layer_min_bytes
+                         for p, q in ranges)
+    return dict(ms_per_step=ms_per_step, ffn_in_ms=ffn_in_ms, calls_ms=calls_ms, counts=counts, cost=launch_cost,
+                step_flops=step_flops, step_min_bytes=step_min_bytes, serial_ms=serial_ms)
 
 
 def roofline_entry(cfg, cost, ffn_in_ms, R):
@@ -148,25 +183,29 @@ def cpu_baseline(cfg, seed, W, x, logits, oracle_mod, sample_tokens):
             "host_cpus": os.cpu_count()}
 
 
-def result_line(cfg, steps, warmup, ms_per_step, ffn_in_ms, calls_ms, counts, cost, R, cpu):
-    tokens_per_s = cfg.T / (ms_per_step * 1e-3)
+def result_line(cfg, steps, warmup, r, R, cpu):
+    ms_per_step, counts, cost = r["ms_per_step"], r["counts"], r["cost"]
+    sec = ms_per_step * 1e-3
     line = {
         "metric": "MoE-layer tokens/sec (route+dispatch+expert FFN+combine), 1 MI355X",
-        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "value": round(cfg.T / sec, 1), "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "f": cfg.f, "E": cfg.E, "k": cfg.k,
-                   "tokens_per_expert_mean": cfg.T * cfg.k / cfg.E, "tokens_per_expert_max": int(counts.max()),
-                   "tokens_per_expert_min": int(counts.min())},
-        "roofline": roofline_entry(cfg, cost, ffn_in_ms, R),
+                   "micro_batches": cfg.micro_batches,
+                   "tokens_per_expert_mean": cfg.T * cfg.k / cfg.E / cfg.micro_batches,
+                   "tokens_per_expert_max": int(counts.max()), "tokens_per_expert_min": int(counts.min())},
+        "roofline": roofline_entry(cfg, cost, r["ffn_in_ms"], R),
         "cpu_baseline": cpu,
-        "layer": {"tflops": round(cost.flops / (ms_per_step * 1e-3) / 1e12, 2),
-                  "min_bytes": cost.layer_min_bytes,
-                  "hbm_frac_of_min_bytes": round(cost.layer_min_bytes / (ms_per_step * 1e-3) / R.MI355X_HBM_BYTES_PER_S, 4),
-                  "mfma_frac": round(cost.flops / (ms_per_step * 1e-3) / R.MI355X_BF16_DENSE_FLOPS, 4)
+        "layer": {"tflops": round(r["step_flops"] / sec / 1e12, 2),
+                  "min_bytes": r["step_min_bytes"],
+                  "hbm_frac_of_min_bytes": round(r["step_min_bytes"] / sec / R.MI355X_HBM_BYTES_PER_S, 4),
+                  "mfma_frac": round(r["step_flops"] / sec / R.MI355X_BF16_DENSE_FLOPS, 4)
                   if cfg.dtype == "bf16" else None,
-                  "calls_ms": {k: round(v, 5) for k, v in calls_ms.items()}},
+                  "calls_ms": {k: round(v, 5) for k, v in r["calls_ms"].items()}},
     }
+    if r["serial_ms"] is not None:
+        line["layer"]["one_stream_ms_per_step"] = round(r["serial_ms"], 5)
     return line
 
 
@@ -221,27 +260,32 @@ def main():
 
     sweep_T = list(synth.MIXTRAL_SWEEP_T) if args.sweep else []
     T_max = max([cfg.T] + (sweep_T if cfg.name.startswith("mixtral") else []))
-    path = B.MoEPath(T_max, cfg.d, cfg.f, cfg.E, cfg.k, cfg.dtype)
-    W, gen_s = upload_and_pack(cfg, args.seed, path, torch, synth)
+    if cfg.micro_batches > 1:
+        T_max = max(b - a for a, b in synth.microbatch_ranges(cfg.T, cfg.micro_batches))
+    paths = [B.MoEPath(T_max, cfg.d, cfg.f, cfg.E, cfg.k, cfg.dtype) for _ in range(2 if cfg.micro_batches > 1 else 1)]
+    W, gen_s = upload_and_pack(cfg, args.seed, paths[0], torch, synth)
+    for p in paths[1:]:
+        p.packed = paths[0].packed          # one packed weight set serves every stream
     print(f"[bench] weights generated in {gen_s:.1f} s and packed", file=sys.stderr, flush=True)
 
     def run(c, want_cpu):
         x, logits = make_inputs(c, args.seed, synth)
         x_d, l_d = dev(x, torch), dev(logits, torch)
-        ms, ffn_ms, calls_ms, counts, cost = time_workload(c, path, x_d, l_d, args.steps, args.warmup, torch, R)
+        r = time_workload(c, paths, x_d, l_d, args.steps, args.warmup, torch, R, synth)
         cpu = None
         if want_cpu:
             print("[bench] timing the CPU oracle on a sample ...", file=sys.stderr, flush=True)
             from oracle import moe_oracle  # the cpu_baseline leg is the only user of the oracle here
             cpu = cpu_baseline(c, args.seed, W, x, logits, moe_oracle, args.cpu_sample_tokens)
-        return result_line(c, args.steps, args.warmup, ms, ffn_ms, calls_ms, counts, cost, R, cpu)
+        return result_line(c, args.steps, args.warmup, r, R, cpu)
 
     if args.sweep and cfg.name.startswith("mixtral"):
         for T in sweep_T:
             if T != cfg.T:
                 print(json.dumps(run(cfg.with_T(T), False)), flush=True)
     print(json.dumps(run(cfg, not args.no_cpu_baseline)), flush=True)
-    path.close()
+    for p in paths:
+        p.close()
 
 
 if __name__ == "__main__":

@@ -34,14 +34,17 @@ __device__ __forceinline__ void static_for(F&& f) {
 struct TileLoc {
   int expert;   // -1: this workgroup has no tile
   int row0;     // first row of the m-tile
-  int row_end;  // end of the expert's segment
+  int rows;     // rows of the m-tile (<= BM)
   int within;   // position inside the expert's block of `per_tile`-sized groups (see locate_tile)
 };
 
-// Work items are ordered expert-major: expert e owns ceil(c_e / BM) * per_tile consecutive
-// positions. Position q inside an expert's block maps to m-tile q % tiles_e and `within`
-// = q / tiles_e, so the m-tiles that share one group of weight columns are neighbours.
+// Work items are ordered expert-major: expert e owns tiles_e * per_tile consecutive positions,
+// tiles_e = ceil(c_e / BM). Position q inside an expert's block maps to m-tile q % tiles_e and
+// `within` = q / tiles_e, so the m-tiles that share one group of weight columns are neighbours.
+// BALANCED: the expert's rows are split evenly over its tiles in multiples of 32 rows (so
+// 1072 rows with BM = 256 become 224 + 224 + 224 + 224 + 176, not 4 x 256 + 48).
 // All threads of the workgroup (>= 256, one per expert) must call this.
+template <bool BALANCED>
 __device__ __forceinline__ TileLoc locate_tile(const int32_t* __restrict__ offsets, int E, int BM, int per_tile,
                                                int pos) {
   __shared__ int s_wave_total[8];
@@ -67,16 +70,18 @@ __device__ __forceinline__ TileLoc locate_tile(const int32_t* __restrict__ offse
   const int first = excl * per_tile;
   if (nt > 0 && pos >= first && pos < first + nt * per_tile) {
     const int q = pos - first;
+    const int step = BALANCED ? (((hi - lo + nt - 1) / nt + 31) & ~31) : BM;  // rows per tile
+    const int r0 = lo + (q % nt) * step;
     s_loc[0] = tid;
-    s_loc[1] = lo + (q % nt) * BM;
-    s_loc[2] = hi;
+    s_loc[1] = r0;
+    s_loc[2] = max(0, min(step, hi - r0));
     s_loc[3] = q / nt;
   }
   __syncthreads();
   TileLoc t;
   t.expert = s_loc[0];
   t.row0 = s_loc[1];
-  t.row_end = s_loc[2];
+  t.rows = s_loc[2];
   t.within = s_loc[3];
   return t;
 }
@@ -118,8 +123,8 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint4* __restrict_
 // K is walked in chunks of 64 (4 MFMA k-steps).
 //
 // Grid (1-D), made for 8 XCDs with one L2 each: workgroups are dealt to XCDs round-robin, so id % 8
-// is the XCD and id / 8 the position in that XCD's queue. Each XCD owns the weight-unit groups
-// g = 8 * j + xcd; its queue is expert-major, then j, then m-tile: the m-tiles of one expert that
+// is the XCD and id / 8 the position in that XCD's queue. For expert e each XCD owns the weight-unit
+// groups g = 8 * j + (xcd + e) % 8; its queue is expert-major, then j, then m-tile: the m-tiles of one expert that
 // read the same weights run next to each other on one L2, and no weight line is wanted by two XCDs.
 //
 // Pipeline. Global loads return in order, so one register ring of NST chunks carries both
@@ -228,9 +233,9 @@ __global__ __launch_bounds__(64 * WN * WM) void ffn_bf16_kernel(const u32x4* __r
   const int groups = (units + WN - 1) / WN;
   const int groups_per_xcd = (groups + 7) / 8;
   const int xcd = blockIdx.x & 7;
-  const TileLoc loc = locate_tile(offsets, E, BM, groups_per_xcd, blockIdx.x >> 3);
+  const TileLoc loc = locate_tile<false>(offsets, E, BM, groups_per_xcd, blockIdx.x >> 3);
   if (loc.expert < 0) return;
-  const int group = loc.within * 8 + xcd;
+  const int group = loc.within * 8 + ((xcd + loc.expert) & 7);  // rotate per expert: evens out a group count that is not a multiple of 8
   if (group >= groups) return;
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -238,7 +243,7 @@ __global__ __launch_bounds__(64 * WN * WM) void ffn_bf16_kernel(const u32x4* __r
   const int KS = K / 16, KV = K / 8;
   const int unit = group * WN + wn;
   const bool has_n = unit < units;
-  const int rows = min(loc.row_end - loc.row0, BM);
+  const int rows = loc.rows;
 
   G g;
   g.slab = slab;
@@ -304,23 +309,30 @@ __global__ __launch_bounds__(64 * WN * WM) void ffn_bf16_kernel(const u32x4* __r
 // bf16 grouped GEMM for large per-expert batches (matrix-core bound).
 //
 // Workgroup = 4 wavefronts, one per SIMD with the whole 512-entry register file: wavefront w owns
-// fragment pair `4 * group + w` and all 256 rows of the m-tile (2 x 8 accumulator tiles = 256
-// registers). Same grid order and weight layout as above; weights come with ordinary (cached)
+// fragment pair `4 * group + w` and all rows of an m-tile of up to kWideBM = 256 rows (up to
+// 2 x 8 accumulator tiles = 256 registers). An expert's rows are split evenly over ceil(c_e / 256) tiles in
+// multiples of 32, so a tile has MU = 1..8 live 32-row groups and nothing is padded beyond the
+// last group. Same grid order and weight layout as above; weights come with ordinary (cached)
 // loads because the m-tiles of an expert share them through L2.
 //
 // With one wavefront per SIMD nothing hides LDS latency but the wavefront's own schedule, so the
-// k-step loop is software-pipelined by hand: the 8 token fragments of k-step s + 1 are read while
-// the 16 MFMAs of k-step s issue (one ds_read per two MFMAs), which the compiler would otherwise
-// undo; a scheduling barrier at every k-step boundary plus per-k-step group barriers pin that
-// order. The slab is triple-buffered: stage c reads buffer c % 3, reads the first fragments of
-// chunk c + 1 from buffer (c + 1) % 3 before the stage's barrier, and writes the tokens of chunk
-// c + 2 into buffer (c + 2) % 3, so no MFMA waits on LDS right after a barrier.
-// MU (2, 4, 6 or 8) = 32-row groups that hold real rows, rounded up to even; the rest are skipped.
+// k-step loop is software-pipelined by hand: token fragments are read R - 1 (row group, k-step)
+// items ahead of the two MFMAs that consume them, through a ring of R fragment registers (the
+// compiler on its own sinks every ds_read next to its use); a scheduling barrier at every k-step
+// boundary plus per-k-step group barriers pin that order. The slab is triple-buffered: stage c
+// reads buffer c % 3, takes the first fragments of chunk c + 1 from buffer (c + 1) % 3 before the
+// stage's barrier, and writes the tokens of chunk c + 2 into buffer (c + 2) % 3, so no MFMA waits
+// on LDS right after a barrier.
+constexpr int kWideBM = 256;
+
 template <bool GATEUP, int MU, int NST>
 __device__ __forceinline__ void wide_tile(const u32x4* __restrict__ X, const u32x4* __restrict__ wbase,
                                           __bf16* __restrict__ C, u32x4* __restrict__ slab, int row0, int rows, int N,
                                           int K, int pair, bool has_n) {
-  constexpr int BM = 256, BUF = BM * 8;
+  constexpr int BUF = kWideBM * 8;            // 16-byte units per slab buffer
+  constexpr int R = (MU % 2 == 0) ? 8 : 4;    // fragment ring; divides the 4 * MU items of a stage
+  constexpr int D = R - 1;                    // read-ahead distance in items
+  constexpr int ITEMS = 4 * MU;
   const int tid = threadIdx.x, lane = tid & 63;
   const int NC = K / 64, KV = K / 8;
   const int trow = tid >> 3, tunit = tid & 7;
@@ -335,7 +347,7 @@ __device__ __forceinline__ void wide_tile(const u32x4* __restrict__ X, const u32
 
   u32x4 wreg[NST][8];
   u32x4 treg[MU];
-  bf16x8 bfr[2][MU];
+  bf16x8 bfr[R];
   floatx16 acc[2][MU];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -359,8 +371,12 @@ __device__ __forceinline__ void wide_tile(const u32x4* __restrict__ X, const u32
     wreg[st][2 * s] = wbase[(size_t)(c * 4 + s) * 128];
     wreg[st][2 * s + 1] = wbase[(size_t)(c * 4 + s) * 128 + 64];
   };
+  // fragment of item it = s * MU + m of the chunk in buffer `boff`
+  auto frag = [&](int boff, int it) {
+    return __builtin_bit_cast(bf16x8, slab[boff + (it % MU) * 256 + rd[it / MU]]);
+  };
 
-  // prologue: chunks 0 and 1 to LDS, chunk 2 in flight, weights of chunks 0 and 1 in flight
+  // prologue: chunks 0 and 1 to LDS, chunk 2 in flight, weights of the first NST chunks in flight
   load_t(0);
   store_t(0);
   load_t(1);
@@ -372,7 +388,7 @@ __device__ __forceinline__ void wide_tile(const u32x4* __restrict__ X, const u32
   });
   __syncthreads();
 #pragma unroll
-  for (int m = 0; m < MU; ++m) bfr[0][m] = __builtin_bit_cast(bf16x8, slab[m * 256 + rd[0]]);
+  for (int it = 0; it < D; ++it) bfr[it % R] = frag(0, it);  // D <= ITEMS for every MU >= 2; MU = 1: D = 3 < 4
 
   int cur = 0, nxt = BUF, wr = 2 * BUF;
   auto stage = [&](auto st_, int c) {
@@ -381,17 +397,19 @@ __device__ __forceinline__ void wide_tile(const u32x4* __restrict__ X, const u32
     for (int s = 0; s < 4; ++s) {
 #pragma unroll
       for (int m = 0; m < MU; ++m) {
-        if (s < 3) bfr[(s + 1) & 1][m] = __builtin_bit_cast(bf16x8, slab[cur + m * 256 + rd[s + 1]]);
-        else bfr[0][m] = __builtin_bit_cast(bf16x8, slab[nxt + m * 256 + rd[0]]);
-        acc[0][m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wreg[st][2 * s]),
-                                                            bfr[s & 1][m], acc[0][m], 0, 0, 0);
+        const int it = s * MU + m;
+        // read ahead: item it + D of this chunk, or of the next chunk's buffer past the end
+        if (it + D < ITEMS) bfr[(it + D) % R] = frag(cur, it + D);
+        else bfr[(it + D) % R] = frag(nxt, it + D - ITEMS);
+        acc[0][m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wreg[st][2 * s]), bfr[it % R],
+                                                            acc[0][m], 0, 0, 0);
         acc[1][m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wreg[st][2 * s + 1]),
-                                                            bfr[s & 1][m], acc[1][m], 0, 0, 0);
+                                                            bfr[it % R], acc[1][m], 0, 0, 0);
       }
       if (s == 0) {
         // token loads go out before this stage's weight loads: loads return in order, and waiting
         // for these tokens one stage from now must not wait for weights needed NST stages from now
-        store_t(wr);      // tokens of chunk c + 2
+        store_t(wr);  // tokens of chunk c + 2
         load_t(c + 3);
       }
       load_w_step(st_, c + NST, s);  // this k-step's weight registers are free again
@@ -445,34 +463,29 @@ __global__ __launch_bounds__(256) void ffn_bf16_wide_kernel(const u32x4* __restr
                                                            const int32_t* __restrict__ offsets,
                                                            const u32x4* __restrict__ Wp, __bf16* __restrict__ C, int E,
                                                            int N, int K) {
-  constexpr int BM = 256;
-  __shared__ u32x4 slab[3 * BM * 8];
+  __shared__ u32x4 slab[3 * kWideBM * 8];
   const int NP = GATEUP ? N / 32 : N / 64;
   const int groups = (NP + 3) / 4;
   const int groups_per_xcd = (groups + 7) / 8;
   const int xcd = blockIdx.x & 7;
-  const TileLoc loc = locate_tile(offsets, E, BM, groups_per_xcd, blockIdx.x >> 3);
+  const TileLoc loc = locate_tile<true>(offsets, E, kWideBM, groups_per_xcd, blockIdx.x >> 3);
   if (loc.expert < 0) return;
-  const int group = loc.within * 8 + xcd;
-  if (group >= groups) return;
+  const int group = loc.within * 8 + ((xcd + loc.expert) & 7);  // rotate per expert: evens out a group count that is not a multiple of 8
+  if (group >= groups || loc.rows <= 0) return;
   const int pair = group * 4 + (threadIdx.x >> 6);
   const bool has_n = pair < NP;
-  const int rows = min(loc.row_end - loc.row0, BM);
+  const int rows = loc.rows;
   const u32x4* wbase = Wp + ((size_t)loc.expert * NP + (has_n ? pair : 0)) * (K / 16) * 128 + (threadIdx.x & 63);
-  const int mu = __builtin_amdgcn_readfirstlane((rows + 63) / 64);  // pairs of 32-row groups
+  const int mu = __builtin_amdgcn_readfirstlane((rows + 31) / 32);  // live 32-row groups, 1..8
   // small tiles have registers to spare: a deeper weight ring keeps them streaming (K / 64 must divide by it)
   const bool deep = (K % 256) == 0;
-  if (mu == 1) {
-    if (deep) wide_tile<GATEUP, 2, 4>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
-    else wide_tile<GATEUP, 2, 2>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
-  } else if (mu == 2) {
-    if (deep) wide_tile<GATEUP, 4, 4>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
-    else wide_tile<GATEUP, 4, 2>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
-  } else if (mu == 3) {
-    wide_tile<GATEUP, 6, 2>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
-  } else {
-    wide_tile<GATEUP, 8, 2>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
-  }
+  static_for<1, kWideBM / 32 + 1>([&](auto mu_) {
+    constexpr int MU = decltype(mu_)::value;
+    if (mu == MU) {
+      if (MU <= 4 && deep) wide_tile<GATEUP, MU, 4>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
+      else wide_tile<GATEUP, MU, 2>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
+    }
+  });
 }
 
 // ------------------------------------------------------------------------------------------
@@ -486,10 +499,10 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ 
   __shared__ float xs[BM][BK + 1];
   __shared__ float ws[NW][BN][BK + 1];
 
-  const TileLoc loc = locate_tile(offsets, E, BM, 1, blockIdx.y);
+  const TileLoc loc = locate_tile<false>(offsets, E, BM, 1, blockIdx.y);
   if (loc.expert < 0) return;
   const int tid = threadIdx.x, tx = tid & 63, ty = tid >> 6;
-  const int rows = min(loc.row_end - loc.row0, BM);
+  const int rows = loc.rows;
   const int n0 = blockIdx.x * BN;
 
   float acc[NW][8];
@@ -566,7 +579,7 @@ void launch_bf16_wide(const void* X, const int32_t* offsets, const void* Wp, voi
                       hipStream_t stream) {
   const int NP = GATEUP ? N / 32 : N / 64;
   const int groups_per_xcd = ((NP + 3) / 4 + 7) / 8;
-  const dim3 grid(8 * groups_per_xcd * max_m_tiles(A, E, 256)), block(256);
+  const dim3 grid(8 * groups_per_xcd * max_m_tiles(A, E, kWideBM)), block(256);
   hipLaunchKernelGGL((ffn_bf16_wide_kernel<GATEUP>), grid, block, 0, stream, static_cast<const u32x4*>(X), offsets,
                      static_cast<const u32x4*>(Wp), static_cast<__bf16*>(C), E, N, K);
 }
