@@ -36,6 +36,7 @@ struct TileLoc {
   int row0;     // first row of the m-tile
   int rows;     // rows of the m-tile (<= BM)
   int within;   // position inside the expert's block of `per_tile`-sized groups (see locate_tile)
+  int tiles;    // m-tiles of this expert
 };
 
 // Work items are ordered expert-major: expert e owns tiles_e * per_tile consecutive positions,
@@ -48,7 +49,7 @@ template <bool BALANCED>
 __device__ __forceinline__ TileLoc locate_tile(const int32_t* __restrict__ offsets, int E, int BM, int per_tile,
                                                int pos) {
   __shared__ int s_wave_total[8];
-  __shared__ int s_loc[4];
+  __shared__ int s_loc[5];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   int lo = 0, hi = 0;
   if (tid < E) {
@@ -76,6 +77,7 @@ __device__ __forceinline__ TileLoc locate_tile(const int32_t* __restrict__ offse
     s_loc[1] = r0;
     s_loc[2] = max(0, min(step, hi - r0));
     s_loc[3] = q / nt;
+    s_loc[4] = nt;
   }
   __syncthreads();
   TileLoc t;
@@ -83,6 +85,7 @@ __device__ __forceinline__ TileLoc locate_tile(const int32_t* __restrict__ offse
   t.row0 = s_loc[1];
   t.rows = s_loc[2];
   t.within = s_loc[3];
+  t.tiles = s_loc[4];
   return t;
 }
 
@@ -312,8 +315,7 @@ __global__ __launch_bounds__(64 * WN * WM) void ffn_bf16_kernel(const u32x4* __r
 // fragment pair `4 * group + w` and all rows of an m-tile of up to kWideBM = 256 rows (up to
 // 2 x 8 accumulator tiles = 256 registers). An expert's rows are split evenly over ceil(c_e / 256) tiles in
 // multiples of 32, so a tile has MU = 1..8 live 32-row groups and nothing is padded beyond the
-// last group. Same grid order and weight layout as above; weights come with ordinary (cached)
-// loads because the m-tiles of an expert share them through L2.
+// last group. Same grid order and weight layout as above.
 //
 // With one wavefront per SIMD nothing hides LDS latency but the wavefront's own schedule, so the
 // k-step loop is software-pipelined by hand: token fragments are read R - 1 (row group, k-step)
@@ -325,7 +327,7 @@ __global__ __launch_bounds__(64 * WN * WM) void ffn_bf16_kernel(const u32x4* __r
 // on LDS right after a barrier.
 constexpr int kWideBM = 256;
 
-template <bool GATEUP, int MU, int NST>
+template <bool GATEUP, int MU, int NST, bool NTL>
 __device__ __forceinline__ void wide_tile(const u32x4* __restrict__ X, const u32x4* __restrict__ wbase,
                                           __bf16* __restrict__ C, u32x4* __restrict__ slab, int row0, int rows, int N,
                                           int K, int pair, bool has_n) {
@@ -368,8 +370,9 @@ __device__ __forceinline__ void wide_tile(const u32x4* __restrict__ X, const u32
   auto load_w_step = [&](auto st_, int c, int s) {
     constexpr int st = decltype(st_)::value;
     c = min(c, NC - 1);
-    wreg[st][2 * s] = wbase[(size_t)(c * 4 + s) * 128];
-    wreg[st][2 * s + 1] = wbase[(size_t)(c * 4 + s) * 128 + 64];
+    const u32x4* p = wbase + (size_t)(c * 4 + s) * 128;
+    wreg[st][2 * s] = NTL ? __builtin_nontemporal_load(p) : p[0];
+    wreg[st][2 * s + 1] = NTL ? __builtin_nontemporal_load(p + 64) : p[64];
   };
   // fragment of item it = s * MU + m of the chunk in buffer `boff`
   auto frag = [&](int boff, int it) {
@@ -477,13 +480,21 @@ __global__ __launch_bounds__(256) void ffn_bf16_wide_kernel(const u32x4* __restr
   const int rows = loc.rows;
   const u32x4* wbase = Wp + ((size_t)loc.expert * NP + (has_n ? pair : 0)) * (K / 16) * 128 + (threadIdx.x & 63);
   const int mu = __builtin_amdgcn_readfirstlane((rows + 31) / 32);  // live 32-row groups, 1..8
-  // small tiles have registers to spare: a deeper weight ring keeps them streaming (K / 64 must divide by it)
+  // Tiles of up to 5 row groups have registers to spare for a deeper weight ring (K / 64 must divide
+  // by it). An expert with a single m-tile reads its weights once: non-temporal loads, as in the
+  // streaming kernel; otherwise cached loads, since the expert's m-tiles share the weights in L2.
   const bool deep = (K % 256) == 0;
+  const bool once = loc.tiles == 1;
   static_for<1, kWideBM / 32 + 1>([&](auto mu_) {
     constexpr int MU = decltype(mu_)::value;
     if (mu == MU) {
-      if (MU <= 4 && deep) wide_tile<GATEUP, MU, 4>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
-      else wide_tile<GATEUP, MU, 2>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
+      if (once && MU <= 6) {  // (the 7- and 8-group variants have no registers left for it)
+        if (MU <= 5 && deep) wide_tile<GATEUP, MU, 4, true>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
+        else wide_tile<GATEUP, MU, 2, true>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
+      } else {
+        if (MU <= 5 && deep) wide_tile<GATEUP, MU, 4, false>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
+        else wide_tile<GATEUP, MU, 2, false>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
+      }
     }
   });
 }
