@@ -217,6 +217,10 @@ def main():
     ap.add_argument("--workload", default="mixtral_T256")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--sweep", action="store_true", help="also run the Mixtral-shaped T sweep (one line per T)")
+    ap.add_argument("--micro-batches", type=int, default=0,
+                    help="override the workload's micro-batch count m (m > 1: two alternating streams)")
+    ap.add_argument("--fit", action="store_true",
+                    help="with --sweep: fit the paper's expert-time model T_e = k3*b_e + k4 to the measured FFN times")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=256)
     ap.add_argument("--calibrate", action="store_true",
@@ -258,6 +262,9 @@ def main():
     else:
         raise SystemExit(f"unknown workload {args.workload!r}; known: {sorted(synth.CONFIGS)} and mixtral_T<N>")
 
+    if args.micro_batches > 0:
+        from dataclasses import replace
+        cfg = replace(cfg, micro_batches=args.micro_batches, name=f"{cfg.name}_m{args.micro_batches}")
     sweep_T = list(synth.MIXTRAL_SWEEP_T) if args.sweep else []
     T_max = max([cfg.T] + (sweep_T if cfg.name.startswith("mixtral") else []))
     if cfg.micro_batches > 1:
@@ -279,11 +286,21 @@ def main():
             cpu = cpu_baseline(c, args.seed, W, x, logits, moe_oracle, args.cpu_sample_tokens)
         return result_line(c, args.steps, args.warmup, r, R, cpu)
 
+    lines = []
     if args.sweep and cfg.name.startswith("mixtral"):
         for T in sweep_T:
             if T != cfg.T:
-                print(json.dumps(run(cfg.with_T(T), False)), flush=True)
-    print(json.dumps(run(cfg, not args.no_cpu_baseline)), flush=True)
+                lines.append(run(cfg.with_T(T), False))
+                print(json.dumps(lines[-1]), flush=True)
+    lines.append(run(cfg, not args.no_cpu_baseline))
+    if args.fit and len(lines) >= 4:
+        # expert time of one layer call = the two FFN GEMMs; b_e = mean tokens per expert
+        pts = sorted((l["config"]["tokens_per_expert_mean"],
+                      l["layer"]["calls_ms"]["ffn_input"] + l["layer"]["calls_ms"]["ffn_output"]) for l in lines)
+        fit = R.fit_expert_time([p[0] for p in pts], [p[1] for p in pts], split=128)
+        fit["roofline_ridge_b"] = R.ridge_batch(R.MI355X_BF16_DENSE_FLOPS, R.MI355X_HBM_BYTES_PER_S)
+        print(json.dumps({"expert_time_model": "T_e[ms] = k3*b_e + k4", "points": pts, "fit": fit}), flush=True)
+    print(json.dumps(lines[-1]), flush=True)
     for p in paths:
         p.close()
 

@@ -94,3 +94,37 @@ def layer_cost(T: int, d: int, f: int, E: int, k: int, elem_bytes: int, active_e
         combine_bytes=A * d * s + T * d * s + 8 * A,
         layer_min_bytes=w_in + w_out + 2 * T * d * s + T * E * 4,
     )
+
+
+def fit_linear(b, t):
+    """Least-squares line t = k3*b + k4 through points (b_i, t_i); returns (k3, k4, max relative residual).
+
+    This is the paper's expert-time model T_e = k3*b_e + k4 (Section 4.2, "Performance simulation"),
+    whose constants it obtains by profiling."""
+    n = len(b)
+    if n < 2 or n != len(t):
+        raise ValueError("need at least two (b, t) points")
+    mb, mt = sum(b) / n, sum(t) / n
+    sxx = sum((x - mb) ** 2 for x in b)
+    if sxx == 0:
+        raise ValueError("all b equal")
+    k3 = sum((x - mb) * (y - mt) for x, y in zip(b, t)) / sxx
+    k4 = mt - k3 * mb
+    resid = max(abs(k3 * x + k4 - y) / y for x, y in zip(b, t))
+    return k3, k4, resid
+
+
+def fit_expert_time(b, t, split: float):
+    """Fit T_e(b_e) as the paper's single line and as two regimes (b <= split: weight-streaming,
+    b > split: compute) and return both, with the batch at which the two regime lines cross (the
+    measured ridge, to be compared with the roofline's F/B)."""
+    lo = [(x, y) for x, y in zip(b, t) if x <= split]
+    hi = [(x, y) for x, y in zip(b, t) if x > split]
+    out = {"single": dict(zip(("k3", "k4", "max_rel_resid"), fit_linear(b, t)))}
+    if len(lo) >= 2 and len(hi) >= 2:
+        a1, c1, r1 = fit_linear(*zip(*lo))
+        a2, c2, r2 = fit_linear(*zip(*hi))
+        out["streaming"] = {"k3": a1, "k4": c1, "max_rel_resid": r1}
+        out["compute"] = {"k3": a2, "k4": c2, "max_rel_resid": r2}
+        out["crossover_b"] = (c1 - c2) / (a2 - a1) if a2 != a1 else None
+    return out

@@ -57,3 +57,14 @@ def test_layer_cost_mixtral_decode():
     assert c.staged_bytes > c.layer_min_bytes
     # fewer active experts -> fewer weight bytes
     assert R.layer_cost(2, 6144, 16384, 8, 2, 2).weight_bytes == 3 * 6144 * 16384 * 2 * 4
+
+
+def test_expert_time_fit_recovers_a_known_line_and_crossover():
+    b = [8, 16, 32, 64, 128, 512, 1024, 2048]
+    t = [0.75 + 1e-4 * x for x in b[:5]] + [0.2 + 1.3e-3 * x for x in b[5:]]
+    k3, k4, resid = R.fit_linear(b[5:], t[5:])
+    assert abs(k3 - 1.3e-3) < 1e-12 and abs(k4 - 0.2) < 1e-9 and resid < 1e-9
+    fit = R.fit_expert_time(b, t, split=128)
+    assert abs(fit["streaming"]["k3"] - 1e-4) < 1e-12 and abs(fit["streaming"]["k4"] - 0.75) < 1e-9
+    assert abs(fit["crossover_b"] - (0.75 - 0.2) / (1.3e-3 - 1e-4)) < 1e-6
+    assert fit["single"]["max_rel_resid"] > 0.01          # one line does not describe both regimes
