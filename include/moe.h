@@ -91,6 +91,19 @@ moe_status moe_route(moe_ctx* ctx, int32_t T, const float* logits, int32_t* topk
                      int32_t* counts, int32_t* offsets, void* stream);
 
 /*
+ * Gating GEMM fused with the routing (Section 2.2: the gate scores are a matrix multiplication of
+ * each token's embedding with the gating parameters; Section 6 "Fused kernels": the paper fuses the
+ * top-k, the per-expert counts and the normalised weights with the gating computation).
+ * In: x[T, d] (cfg.dtype), w_router[E, d] float32.
+ *     logits[t, e] = sum_c x[t, c] * w_router[e, c], accumulated in float32
+ * Out: logits[T, E] float32 (may be NULL: then the scores never leave the chip), and topk_idx,
+ * topk_w, counts, offsets exactly as moe_route would give on those logits. Two launches instead
+ * of the three of a separate gate GEMM followed by moe_route.
+ */
+moe_status moe_gate_route(moe_ctx* ctx, int32_t T, const void* x, const float* w_router, float* logits,
+                          int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* offsets, void* stream);
+
+/*
  * Dispatch pack (Section 2.2 "send input tokens to the experts"; Section 6 "scatter tokens to
  * respective experts"): stable counting sort of the A assignments by expert.
  * In: x[T, d], topk_idx[T, k], offsets[E + 1] (as written by moe_route).

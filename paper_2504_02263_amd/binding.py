@@ -23,7 +23,7 @@ MOE_F32, MOE_BF16 = 0, 1
 _DTYPES = {"f32": (MOE_F32, torch.float32), "bf16": (MOE_BF16, torch.bfloat16)}
 
 EXPORTS = ("moe_create", "moe_destroy", "moe_last_error", "moe_status_string", "moe_packed_weight_bytes",
-           "moe_pack_weights", "moe_route", "moe_dispatch", "moe_expert_ffn", "moe_ffn_input", "moe_ffn_output",
+           "moe_pack_weights", "moe_route", "moe_gate_route", "moe_dispatch", "moe_expert_ffn", "moe_ffn_input", "moe_ffn_output",
            "moe_combine")
 
 
@@ -62,12 +62,13 @@ def load_library() -> ctypes.CDLL:
     lib.moe_packed_weight_bytes.restype = ctypes.c_size_t
     lib.moe_pack_weights.argtypes = [vp] + [vp] * 4 + [vp]
     lib.moe_route.argtypes = [vp, i32] + [vp] * 5 + [vp]
+    lib.moe_gate_route.argtypes = [vp, i32] + [vp] * 7 + [vp]
     lib.moe_dispatch.argtypes = [vp, i32] + [vp] * 6 + [vp]
     lib.moe_expert_ffn.argtypes = [vp, i32] + [vp] * 5 + [vp]
     lib.moe_ffn_input.argtypes = [vp, i32] + [vp] * 4 + [vp]
     lib.moe_ffn_output.argtypes = [vp, i32] + [vp] * 4 + [vp]
     lib.moe_combine.argtypes = [vp, i32] + [vp] * 4 + [vp]
-    for name in ("moe_pack_weights", "moe_route", "moe_dispatch", "moe_expert_ffn", "moe_ffn_input", "moe_ffn_output",
+    for name in ("moe_pack_weights", "moe_route", "moe_gate_route", "moe_dispatch", "moe_expert_ffn", "moe_ffn_input", "moe_ffn_output",
            "moe_combine"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -125,6 +126,11 @@ def moe_pack_weights(ctx, w_gate, w_up, w_down, packed, stream=None) -> None:
 def moe_route(ctx, T, logits, topk_idx, topk_w, counts, offsets, stream=None) -> None:
     _check(ctx, load_library().moe_route(ctx, T, _ptr(logits), _ptr(topk_idx), _ptr(topk_w), _ptr(counts),
                                          _ptr(offsets), _stream(stream)))
+
+
+def moe_gate_route(ctx, T, x, w_router, logits, topk_idx, topk_w, counts, offsets, stream=None) -> None:
+    _check(ctx, load_library().moe_gate_route(ctx, T, _ptr(x), _ptr(w_router), _ptr(logits), _ptr(topk_idx),
+                                              _ptr(topk_w), _ptr(counts), _ptr(offsets), _stream(stream)))
 
 
 def moe_dispatch(ctx, T, x, topk_idx, offsets, xp, pos, src, stream=None) -> None:
@@ -194,6 +200,10 @@ class MoEPath:
     def route(self, logits, T=None, stream=None):
         T = logits.shape[0] if T is None else T
         moe_route(self.ctx, T, logits, self.topk_idx, self.topk_w, self.counts, self.offsets, stream)
+
+    def gate_route(self, x, w_router, logits=None, T=None, stream=None):
+        T = x.shape[0] if T is None else T
+        moe_gate_route(self.ctx, T, x, w_router, logits, self.topk_idx, self.topk_w, self.counts, self.offsets, stream)
 
     def dispatch(self, x, T=None, stream=None):
         T = x.shape[0] if T is None else T

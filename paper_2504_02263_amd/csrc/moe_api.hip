@@ -112,6 +112,17 @@ moe_status moe_route(moe_ctx* ctx, int32_t T, const float* logits, int32_t* topk
                                   static_cast<hipStream_t>(stream)));
 }
 
+moe_status moe_gate_route(moe_ctx* ctx, int32_t T, const void* x, const float* w_router, float* logits,
+                          int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* offsets, void* stream) {
+  const void* ptrs[] = {x, w_router, topk_idx, topk_w, counts, offsets};
+  const moe_status s = check_call(ctx, "moe_gate_route", T, ptrs, 6);
+  if (s != MOE_OK) return s;
+  if (logits && !aligned16(logits)) return fail(ctx, MOE_ERR_INVALID_ARG, "moe_gate_route: logits is not 16-byte aligned");
+  return finish(ctx, "moe_gate_route",
+                moe::launch_gate_route(x, w_router, T, ctx->cfg.d, ctx->cfg.E, ctx->cfg.k, ctx->cfg.dtype, logits,
+                                       topk_idx, topk_w, counts, offsets, static_cast<hipStream_t>(stream)));
+}
+
 moe_status moe_dispatch(moe_ctx* ctx, int32_t T, const void* x, const int32_t* topk_idx, const int32_t* offsets,
                         void* xp, int32_t* pos, int32_t* src, void* stream) {
   const void* ptrs[] = {x, topk_idx, offsets, xp, pos, src};

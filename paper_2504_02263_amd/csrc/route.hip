@@ -10,35 +10,16 @@ namespace {
 constexpr int kMaxPerLane = 4;  // experts held per lane: E <= 64 * 4
 
 // A group of L lanes (L = 8, 16, 32 or 64, a power of two >= min(E, 64)) owns one token; lane sl
-// of the group holds experts sl, sl + L, sl + 2L, ... The k picks are k rounds of an argmax
+// of the group holds experts sl, sl + L, sl + 2L, ... in v[]. The k picks are k rounds of an argmax
 // butterfly over the group on (value, index) pairs: larger value wins, equal values go to the
 // lower index. After a round every lane of the group knows the winner; its owner retires it.
+// On return lane sl < k holds pick sl and its softmax-over-the-picks weight.
 template <int L>
-__global__ __launch_bounds__(256) void route_topk_kernel(const float* __restrict__ logits, int T, int E, int k,
-                                                         int32_t* __restrict__ topk_idx,
-                                                         float* __restrict__ topk_w) {
-  constexpr int kTokensPerWave = 64 / L;
-  const int lane = threadIdx.x & 63;
-  const int wave = (blockIdx.x * 256 + threadIdx.x) >> 6;
-  const int sl = lane % L;
-  const int t = wave * kTokensPerWave + lane / L;
-  const bool valid = t < T;
-
-  float v[kMaxPerLane];
-#pragma unroll
-  for (int i = 0; i < kMaxPerLane; ++i) {
-    const int e = sl + i * L;
-    float x = -INFINITY;
-    if (valid && e < E) {
-      x = logits[(size_t)t * E + e];
-      if (x != x) x = -INFINITY;  // NaN ranks as -inf
-    }
-    v[i] = x;
-  }
-
+__device__ __forceinline__ void topk_group(const float (&v)[kMaxPerLane], int sl, int E, int k, int& my_idx,
+                                           float& my_w) {
   unsigned taken = 0;
   float row_max = 0.f, sum = 0.f, my_p = 0.f;
-  int my_idx = 0;
+  my_idx = 0;
   for (int j = 0; j < k; ++j) {
     float bv = -INFINITY;
     int bi = INT_MAX;
@@ -68,9 +49,220 @@ __global__ __launch_bounds__(256) void route_topk_kernel(const float* __restrict
       my_idx = bi;
     }
   }
+  my_w = my_p / sum;
+}
+
+template <int L>
+__global__ __launch_bounds__(256) void route_topk_kernel(const float* __restrict__ logits, int T, int E, int k,
+                                                         int32_t* __restrict__ topk_idx,
+                                                         float* __restrict__ topk_w) {
+  constexpr int kTokensPerWave = 64 / L;
+  const int lane = threadIdx.x & 63;
+  const int wave = (blockIdx.x * 256 + threadIdx.x) >> 6;
+  const int sl = lane % L;
+  const int t = wave * kTokensPerWave + lane / L;
+  const bool valid = t < T;
+
+  float v[kMaxPerLane];
+#pragma unroll
+  for (int i = 0; i < kMaxPerLane; ++i) {
+    const int e = sl + i * L;
+    float x = -INFINITY;
+    if (valid && e < E) {
+      x = logits[(size_t)t * E + e];
+      if (x != x) x = -INFINITY;  // NaN ranks as -inf
+    }
+    v[i] = x;
+  }
+  int my_idx;
+  float my_w;
+  topk_group<L>(v, sl, E, k, my_idx, my_w);
   if (valid && sl < k) {
     topk_idx[(size_t)t * k + sl] = my_idx;
-    topk_w[(size_t)t * k + sl] = my_p / sum;
+    topk_w[(size_t)t * k + sl] = my_w;
+  }
+}
+
+// Gating GEMM fused with the top-k (the paper fuses these small memory-bound steps with the gating
+// computation, Section 6 "Fused kernels"): logits[t, e] = sum_c x[t, c] * w_router[e, c] in float32.
+// Workgroup = TT (16 or 32) tokens; thread (tok = tid % TT, eg = tid / TT) accumulates the EPT
+// experts eg * EPT .. of its token over all of d, from LDS tiles of x (widened to float32) and
+// w_router, 64 columns at a time; the next tile's global loads are in flight while the current one
+// is consumed. The finished TT x E logits stay in LDS for the top-k (and go to HBM only if the
+// caller asks for them).
+template <int TT, int EPT, int L, bool BF16>
+__global__ __launch_bounds__(256) void gate_topk_kernel(const void* __restrict__ x_, const float* __restrict__ wr,
+                                                        int T, int d, int E, int k, float* __restrict__ logits,
+                                                        int32_t* __restrict__ topk_idx, float* __restrict__ topk_w) {
+  constexpr int KC = 64, EG = 256 / TT, EMAX = EG * EPT;
+  constexpr int WL = (EMAX * (KC / 4) + 255) / 256;  // float4 loads of the w_router tile per thread
+  __shared__ float xs[TT][KC + 1];
+  __shared__ float ws[EMAX][KC + 1];
+  __shared__ float lg[TT][EMAX + 1];
+  const int tid = threadIdx.x, tok = tid % TT, eg = tid / TT;
+  const int t0 = blockIdx.x * TT;
+  float acc[EPT];
+#pragma unroll
+  for (int j = 0; j < EPT; ++j) acc[j] = 0.f;
+
+  // this thread's share of a tile: x row tid / 8, 8 columns at (tid % 8) * 8; w_router float4 number tid + 256 i
+  const int xr = tid >> 3, xc = (tid & 7) * 8;
+  const bool x_on = xr < TT && t0 + xr < T;
+  uint4 xq = {0u, 0u, 0u, 0u};
+  float4 xf[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+  float4 wq[WL];
+  auto fetch = [&](int k0) {
+    if (x_on) {
+      if (BF16) {
+        xq = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(x_) + (size_t)(t0 + xr) * d + k0 + xc);
+      } else {
+        const float* p = static_cast<const float*>(x_) + (size_t)(t0 + xr) * d + k0 + xc;
+        xf[0] = *reinterpret_cast<const float4*>(p);
+        xf[1] = *reinterpret_cast<const float4*>(p + 4);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < WL; ++i) {
+      const int u = tid + 256 * i, e = u / (KC / 4), c = (u % (KC / 4)) * 4;
+      wq[i] = e < E ? *reinterpret_cast<const float4*>(wr + (size_t)e * d + k0 + c) : float4{0.f, 0.f, 0.f, 0.f};
+    }
+  };
+  auto stash = [&]() {
+    if (xr < TT) {
+      float f[8];
+      if (BF16) {
+        const uint32_t u[4] = {xq.x, xq.y, xq.z, xq.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          f[2 * i] = __uint_as_float(u[i] << 16);
+          f[2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
+        }
+      } else {
+        f[0] = xf[0].x; f[1] = xf[0].y; f[2] = xf[0].z; f[3] = xf[0].w;
+        f[4] = xf[1].x; f[5] = xf[1].y; f[6] = xf[1].z; f[7] = xf[1].w;
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) xs[xr][xc + i] = f[i];
+    }
+#pragma unroll
+    for (int i = 0; i < WL; ++i) {
+      const int u = tid + 256 * i, e = u / (KC / 4), c = (u % (KC / 4)) * 4;
+      if (e < EMAX) {
+        ws[e][c] = wq[i].x; ws[e][c + 1] = wq[i].y; ws[e][c + 2] = wq[i].z; ws[e][c + 3] = wq[i].w;
+      }
+    }
+  };
+
+  fetch(0);
+  for (int k0 = 0; k0 < d; k0 += KC) {
+    stash();
+    __syncthreads();
+    if (k0 + KC < d) fetch(k0 + KC);
+#pragma unroll 8
+    for (int kk = 0; kk < KC; ++kk) {
+      const float xv = xs[tok][kk];
+#pragma unroll
+      for (int j = 0; j < EPT; ++j) acc[j] = fmaf(xv, ws[eg * EPT + j][kk], acc[j]);  // rows >= E are zero
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int j = 0; j < EPT; ++j) lg[tok][eg * EPT + j] = acc[j];
+  __syncthreads();
+  if (logits) {
+    for (int u = tid; u < TT * E; u += 256) {
+      const int r = u / E, e = u % E;
+      if (t0 + r < T) logits[(size_t)(t0 + r) * E + e] = lg[r][e];
+    }
+  }
+  // top-k: 256 / L tokens per pass
+  const int sl = tid % L;
+  for (int base = 0; base < TT; base += 256 / L) {
+    const int r = base + tid / L;
+    const bool valid = r < TT && t0 + r < T;
+    float v[kMaxPerLane];
+#pragma unroll
+    for (int i = 0; i < kMaxPerLane; ++i) {
+      const int e = sl + i * L;
+      float q = -INFINITY;
+      if (valid && e < E) {
+        q = lg[r][e];
+        if (q != q) q = -INFINITY;
+      }
+      v[i] = q;
+    }
+    int my_idx;
+    float my_w;
+    topk_group<L>(v, sl, E, k, my_idx, my_w);
+    if (valid && sl < k) {
+      topk_idx[(size_t)(t0 + r) * k + sl] = my_idx;
+      topk_w[(size_t)(t0 + r) * k + sl] = my_w;
+    }
+  }
+}
+
+// The same fusion for few experts (E <= EM = 8 or 16), where the batch is too small to fill the
+// chip with 16-token workgroups: one wavefront per token, lanes stride over d in 16-byte pieces,
+// w_router comes from L2 (E * d * 4 bytes per token), no LDS and no barrier. Lane sums are combined
+// by a butterfly, after which lane e of every EM-lane group holds logit e and the top-k runs in place.
+template <int EM, bool BF16>
+__global__ __launch_bounds__(256) void gate_topk_wave_kernel(const void* __restrict__ x_, const float* __restrict__ wr,
+                                                             int T, int d, int E, int k, float* __restrict__ logits,
+                                                             int32_t* __restrict__ topk_idx,
+                                                             float* __restrict__ topk_w) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;  // whole wavefront
+  float acc[EM];
+#pragma unroll
+  for (int e = 0; e < EM; ++e) acc[e] = 0.f;
+  for (int c = lane * 8; c < d; c += 512) {
+    float f[8];
+    if (BF16) {
+      const uint4 q = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(x_) + (size_t)t * d + c);
+      const uint32_t u[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        f[2 * i] = __uint_as_float(u[i] << 16);
+        f[2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
+      }
+    } else {
+      const float* p = static_cast<const float*>(x_) + (size_t)t * d + c;
+      const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+      f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+    }
+#pragma unroll
+    for (int e = 0; e < EM; ++e) {
+      if (e < E) {
+        const float* p = wr + (size_t)e * d + c;
+        const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+        float s = acc[e];
+        s = fmaf(f[0], a.x, s); s = fmaf(f[1], a.y, s); s = fmaf(f[2], a.z, s); s = fmaf(f[3], a.w, s);
+        s = fmaf(f[4], b.x, s); s = fmaf(f[5], b.y, s); s = fmaf(f[6], b.z, s); s = fmaf(f[7], b.w, s);
+        acc[e] = s;
+      }
+    }
+  }
+  const int sl = lane % EM;
+  float mine = 0.f;
+#pragma unroll
+  for (int e = 0; e < EM; ++e) {
+    float s = acc[e];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+    if (sl == e) mine = s;
+  }
+  if (logits && lane < E) logits[(size_t)t * E + lane] = mine;
+  float v[kMaxPerLane];
+#pragma unroll
+  for (int i = 0; i < kMaxPerLane; ++i) v[i] = -INFINITY;
+  if (sl < E) v[0] = mine != mine ? -INFINITY : mine;
+  int my_idx;
+  float my_w;
+  topk_group<EM>(v, sl, E, k, my_idx, my_w);
+  if (lane < k) {
+    topk_idx[(size_t)t * k + lane] = my_idx;
+    topk_w[(size_t)t * k + lane] = my_w;
   }
 }
 
@@ -129,6 +321,41 @@ hipError_t launch_route(const float* logits, int T, int E, int k, int32_t* topk_
       case 32: hipLaunchKernelGGL(route_topk_kernel<32>, grid, block, 0, stream, logits, T, E, k, topk_idx, topk_w); break;
       default: hipLaunchKernelGGL(route_topk_kernel<64>, grid, block, 0, stream, logits, T, E, k, topk_idx, topk_w); break;
     }
+  }
+  hipLaunchKernelGGL(route_count_kernel, dim3(1), dim3(1024), 0, stream, topk_idx, T * k, E, counts, offsets);
+  return hipGetLastError();
+}
+
+
+template <int TT, int EPT, int L>
+static void launch_gate_topk(bool bf16, hipStream_t stream, const void* x, const float* wr, int T, int d, int E, int k,
+                             float* logits, int32_t* topk_idx, float* topk_w) {
+  const dim3 grid((T + TT - 1) / TT);
+  if (bf16)
+    hipLaunchKernelGGL((gate_topk_kernel<TT, EPT, L, true>), grid, dim3(256), 0, stream, x, wr, T, d, E, k, logits,
+                       topk_idx, topk_w);
+  else
+    hipLaunchKernelGGL((gate_topk_kernel<TT, EPT, L, false>), grid, dim3(256), 0, stream, x, wr, T, d, E, k, logits,
+                       topk_idx, topk_w);
+}
+
+hipError_t launch_gate_route(const void* x, const float* w_router, int T, int d, int E, int k, int dtype, float* logits,
+                             int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* offsets, hipStream_t stream) {
+  if (T > 0) {
+    const bool bf16 = dtype == MOE_BF16;
+    const dim3 wgrid((T + 3) / 4);
+    if (E <= 8) {  // one wavefront per token
+      if (bf16) hipLaunchKernelGGL((gate_topk_wave_kernel<8, true>), wgrid, dim3(256), 0, stream, x, w_router, T, d, E, k, logits, topk_idx, topk_w);
+      else hipLaunchKernelGGL((gate_topk_wave_kernel<8, false>), wgrid, dim3(256), 0, stream, x, w_router, T, d, E, k, logits, topk_idx, topk_w);
+    } else if (E <= 16) {
+      if (bf16) hipLaunchKernelGGL((gate_topk_wave_kernel<16, true>), wgrid, dim3(256), 0, stream, x, w_router, T, d, E, k, logits, topk_idx, topk_w);
+      else hipLaunchKernelGGL((gate_topk_wave_kernel<16, false>), wgrid, dim3(256), 0, stream, x, w_router, T, d, E, k, logits, topk_idx, topk_w);
+    }
+    // more experts: 16-token workgroups (16 expert groups of EPT) while E allows it
+    else if (E <= 32) launch_gate_topk<16, 2, 32>(bf16, stream, x, w_router, T, d, E, k, logits, topk_idx, topk_w);
+    else if (E <= 64) launch_gate_topk<16, 4, 64>(bf16, stream, x, w_router, T, d, E, k, logits, topk_idx, topk_w);
+    else if (E <= 128) launch_gate_topk<32, 16, 64>(bf16, stream, x, w_router, T, d, E, k, logits, topk_idx, topk_w);
+    else launch_gate_topk<32, 32, 64>(bf16, stream, x, w_router, T, d, E, k, logits, topk_idx, topk_w);
   }
   hipLaunchKernelGGL(route_count_kernel, dim3(1), dim3(1024), 0, stream, topk_idx, T * k, E, counts, offsets);
   return hipGetLastError();

@@ -231,3 +231,34 @@ def test_calls_run_on_the_given_stream():
     s.synchronize()
     assert rel_fro(host(path.out), ref["out"]) <= 1e-2
     path.close()
+
+
+# ------------------------------------------------------------------------------- fused gate GEMM + routing
+
+@pytest.mark.parametrize("T,d,E,k,dtype", [(64, 256, 8, 2, "f32"), (257, 384, 16, 4, "bf16"), (1000, 512, 64, 6, "bf16"),
+                                           (70, 128, 100, 7, "bf16"), (33, 256, 256, 8, "f32"), (5, 128, 5, 3, "bf16"),
+                                           (256, 6144, 8, 2, "bf16")])
+def test_gate_route(T, d, E, k, dtype):
+    """moe_gate_route: the gate scores against the oracle's float64 product, and the routing
+    bit-exact against the oracle routed on the very logits the GPU produced."""
+    cfg = small_cfg(T, d, 128, E, k, dtype)
+    x = synth.make_activations(cfg, 4)
+    w_r = synth.make_router_weight(cfg, 4)
+    path = B.MoEPath(T, d, 128, E, k, dtype)
+    logits = torch.full((T, E), 7.0, dtype=torch.float32, device="cuda")
+    path.gate_route(dev(x), dev(w_r), logits)
+    torch.cuda.synchronize()
+    g_logits = host(logits)
+    ref_logits = O.gate_logits(x, w_r)
+    err = float(np.linalg.norm(g_logits - ref_logits.astype(np.float64)) / np.linalg.norm(ref_logits))
+    assert err <= 1e-5, err
+    idx, w, counts, offsets = O.route(g_logits, k)
+    assert (host(path.topk_idx)[:T] == idx).all()
+    assert (host(path.counts) == counts).all() and (host(path.offsets) == offsets).all()
+    np.testing.assert_allclose(host(path.topk_w)[:T], w, rtol=0, atol=W_TOL)
+    # without the logits output the routing is the same
+    first = host(path.topk_idx).copy()
+    path.gate_route(dev(x), dev(w_r), None)
+    torch.cuda.synchronize()
+    assert (host(path.topk_idx) == first).all() and (host(path.counts) == counts).all()
+    path.close()
