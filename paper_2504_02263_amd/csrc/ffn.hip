@@ -10,6 +10,7 @@
 // contiguous per load. Tokens (the other operand) are staged through LDS and shared by the
 // wavefronts of the workgroup. Per-expert row ranges come from `offsets` on the device.
 #include <math.h>
+#include <stdlib.h>
 #include <type_traits>
 #include "moe_internal.h"
 
@@ -205,14 +206,19 @@ struct Gemm {
       __syncthreads();
     };
 
-    // prologue: chunk 0 tokens straight to LDS; then the steady-state issue order W[c], tokens[c + 1]
-    load_t(std::integral_constant<int, 0>{}, 0);
-    store_t(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    // prologue: every first load goes out at once (chunk 0 tokens, then the steady-state issue order
+    // W[c], tokens[c + 1]), so the workgroup pays one memory latency, not two, before its first MFMA
+    u32x4 t0[PASSES];
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) t0[p] = xrow[p][0];
     static_for<0, NST>([&](auto st_) {
       constexpr int st = decltype(st_)::value;
       load_w(st_, st);
       load_t(std::integral_constant<int, (st + 1) % NST>{}, st + 1);
     });
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p)
+      if (BM % RPP == 0 || p * RPP + trow < BM) slab[0][p * RPP * 8 + swz_w] = t0[p];
     __syncthreads();
     // NC is a multiple of NST (K is a multiple of 128 and NST is 2), so there is no remainder loop
     for (int c0 = 0; c0 < NC; c0 += NST) static_for<0, NST>([&](auto st_) { stage(st_, c0 + decltype(st_)::value); });
@@ -351,12 +357,6 @@ __device__ __forceinline__ void wide_tile(const u32x4* __restrict__ X, const u32
   u32x4 treg[MU];
   bf16x8 bfr[R];
   floatx16 acc[2][MU];
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int m = 0; m < MU; ++m)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][m][r] = 0.f;
 
   auto load_t = [&](int c) {
     c = min(c, NC - 1);
@@ -379,17 +379,32 @@ __device__ __forceinline__ void wide_tile(const u32x4* __restrict__ X, const u32
     return __builtin_bit_cast(bf16x8, slab[boff + (it % MU) * 256 + rd[it / MU]]);
   };
 
-  // prologue: chunks 0 and 1 to LDS, chunk 2 in flight, weights of the first NST chunks in flight
-  load_t(0);
-  store_t(0);
-  load_t(1);
-  store_t(BUF);
-  load_t(2);
-  static_for<0, NST>([&](auto st_) {
+  // prologue: all first loads go out at once (tokens of chunks 0, 1, 2, then the weights of the first
+  // NST chunks), so the workgroup pays one memory latency before its first MFMA; chunks 0 and 1 go
+  // to LDS, chunk 2 stays in registers for stage 0
+  {
+    u32x4 t0[MU], t1[MU];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) load_w_step(st_, decltype(st_)::value, s);
-  });
+    for (int p = 0; p < MU; ++p) t0[p] = xrow[p][0];
+#pragma unroll
+    for (int p = 0; p < MU; ++p) t1[p] = xrow[p][min(1, NC - 1) * 8];
+    load_t(2);
+    static_for<0, NST>([&](auto st_) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s) load_w_step(st_, decltype(st_)::value, s);
+    });
+#pragma unroll
+    for (int p = 0; p < MU; ++p) slab[p * 256 + swz_w] = t0[p];
+#pragma unroll
+    for (int p = 0; p < MU; ++p) slab[BUF + p * 256 + swz_w] = t1[p];
+  }
   __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int m = 0; m < MU; ++m)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][m][r] = 0.f;
 #pragma unroll
   for (int it = 0; it < D; ++it) bfr[it % R] = frag(0, it);  // D <= ITEMS for every MU >= 2; MU = 1: D = 3 < 4
 
@@ -633,16 +648,21 @@ hipError_t launch_ffn_stage(const moe_config& cfg, int stage, int T, const void*
     // (non-temporal). Above: the 256-row matrix-core-bound kernel, weights shared through L2.
     const float mean = (float)A / cfg.E;
     const float want = mean + 3.f * sqrtf(mean);
+    // Tuning knob (read once): MOE_FFN_WIDE_ABOVE=<rows> moves the switch-over between the two kernels.
+    static const float wide_above = [] {
+      const char* v = getenv("MOE_FFN_WIDE_ABOVE");
+      return v ? (float)atof(v) : 128.f;
+    }();
     const char* w = static_cast<const char*>(packed) + (stage == 0 ? 0 : 2 * one * 2);
     if (stage == 0) {
       if (want <= 32.f) launch_bf16<1, 2, 2, 8, 1, true, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
       else if (want <= 64.f) launch_bf16<2, 2, 2, 8, 1, true, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
-      else if (want <= 128.f) launch_bf16<4, 2, 2, 8, 1, true, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
+      else if (want <= 128.f || want <= wide_above) launch_bf16<4, 2, 2, 8, 1, true, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
       else launch_bf16_wide<true>(in, offsets, w, out, A, cfg.E, N, K, stream);
     } else {
       if (want <= 32.f) launch_bf16<1, 1, 2, 8, 1, false, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
       else if (want <= 64.f) launch_bf16<2, 1, 2, 8, 1, false, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
-      else if (want <= 128.f) launch_bf16<4, 1, 2, 8, 1, false, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
+      else if (want <= 128.f || want <= wide_above) launch_bf16<4, 1, 2, 8, 1, false, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
       else launch_bf16_wide<false>(in, offsets, w, out, A, cfg.E, N, K, stream);
     }
     return hipGetLastError();

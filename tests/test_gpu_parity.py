@@ -262,3 +262,71 @@ def test_gate_route(T, d, E, k, dtype):
     torch.cuda.synchronize()
     assert (host(path.topk_idx) == first).all() and (host(path.counts) == counts).all()
     path.close()
+
+
+# ------------------------------------------------------------------------------- more edge cases
+
+def test_route_largest_supported_k_and_E():
+    """E = 256 experts with k = 64 picks: four experts per lane, one lane per pick."""
+    T, E, k = 37, 256, 64
+    rng = np.random.default_rng(5)
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    logits[::4] = rng.integers(-2, 3, size=logits[::4].shape).astype(np.float32)
+    idx, w, counts, offsets = O.route(logits, k)
+    path = B.MoEPath(T, 128, 128, E, k, "f32")
+    path.route(dev(logits))
+    torch.cuda.synchronize()
+    assert (host(path.topk_idx) == idx).all() and (host(path.counts) == counts).all()
+    assert (host(path.offsets) == offsets).all()
+    np.testing.assert_allclose(host(path.topk_w), w, rtol=0, atol=W_TOL)
+    path.close()
+
+
+def test_route_nan_and_inf_logits_follow_the_documented_rule():
+    """NaN ranks as -inf; -inf is an ordinary (smallest) value; ties still go to the lower index."""
+    logits = np.array([[np.nan, 1.0, 2.0, np.nan], [-np.inf, -np.inf, 0.5, -np.inf], [np.inf, 1.0, np.inf, 0.0]],
+                      np.float32)
+    canon = np.where(np.isnan(logits), -np.inf, logits).astype(np.float32)
+    idx, _, counts, offsets = O.route(canon, 3)
+    path = B.MoEPath(3, 128, 128, 4, 3, "f32")
+    path.route(dev(logits))
+    torch.cuda.synchronize()
+    assert (host(path.topk_idx) == idx).all()
+    assert idx.tolist() == [[2, 1, 0], [2, 0, 1], [0, 2, 1]]
+    assert (host(path.counts) == counts).all() and (host(path.offsets) == offsets).all()
+    path.close()
+
+
+def test_expert_ffn_equals_its_two_stages_and_is_deterministic():
+    cfg = small_cfg(500, 256, 384, 6, 2, "bf16")
+    x, logits = synth.make_activations(cfg, 6), synth.make_logits(cfg, 6)
+    W = synth.make_all_expert_weights(cfg, 6, workers=4)
+    path = run_layer(cfg, x, logits, W)
+    A = cfg.T * cfg.k
+    h1, y1 = host(path.h)[:A].copy(), host(path.y)[:A].copy()
+    path.h.zero_()
+    path.y.zero_()
+    path.ffn_input(cfg.T)
+    path.ffn_output(cfg.T)
+    torch.cuda.synchronize()
+    assert (host(path.h)[:A] == h1).all() and (host(path.y)[:A] == y1).all()      # bitwise
+    for _ in range(3):
+        path.expert_ffn(cfg.T)
+    torch.cuda.synchronize()
+    assert (host(path.h)[:A] == h1).all() and (host(path.y)[:A] == y1).all()
+    path.close()
+
+
+def test_all_tokens_to_one_expert():
+    """Degenerate routing: every token picks the same experts (k = 2 of 4), so two segments hold
+    all rows and two are empty."""
+    cfg = small_cfg(300, 128, 256, 4, 2, "bf16")
+    x = synth.make_activations(cfg, 8)
+    logits = np.tile(np.array([[5.0, -5.0, 4.0, -6.0]], np.float32), (cfg.T, 1))
+    W = synth.make_all_expert_weights(cfg, 8, workers=4)
+    ref = O.moe_layer(x, logits, cfg.k, lambda e: (W[0][e], W[1][e], W[2][e]))
+    assert ref["counts"].tolist() == [300, 0, 300, 0]
+    path = run_layer(cfg, x, logits, W)
+    check_integers(path, ref, cfg.T, cfg.k)
+    assert rel_fro(host(path.out), ref["out"]) <= 1e-2
+    path.close()
