@@ -153,6 +153,26 @@ def expert_ffn(xp: np.ndarray, offsets: np.ndarray, expert_weights, return_h: bo
     return (y, h_all) if return_h else y
 
 
+def expert_ffn_segments(xp: np.ndarray, seg_begin, seg_end, seg_expert, expert_weights, y=None):
+    """The same per-expert FFN over explicit row ranges: slot s applies expert seg_expert[s] to
+    rows [seg_begin[s], seg_end[s]). This is what one expert node runs when popular experts have
+    several copies, each taking part of the expert's rows (Section 6, "Load balance").
+    Rows outside every range are left as they are in `y` (zeros if y is None). Returns y float64."""
+    get = expert_weights if callable(expert_weights) else (lambda e: expert_weights[e])
+    A, d = xp.shape
+    if y is None:
+        y = np.zeros((A, d), dtype=np.float64)
+    for lo, hi, e in zip(seg_begin, seg_end, seg_expert):
+        lo, hi = int(lo), int(hi)
+        if hi <= lo:
+            continue
+        w_gate, w_up, w_down = get(int(e))
+        rows = widen(xp[lo:hi])
+        h = silu(rows @ widen(w_gate).T) * (rows @ widen(w_up).T)
+        y[lo:hi] = h @ widen(w_down).T
+    return y
+
+
 def combine(y: np.ndarray, pos: np.ndarray, topk_w: np.ndarray) -> np.ndarray:
     """Weighted sum of each token's k expert outputs (Section 2.2):
     out[t, :] = sum_j topk_w[t, j] * y[pos[t, j], :]. Returns float64 [T, d]."""
