@@ -143,6 +143,57 @@ moe_status moe_ffn_output(moe_ctx* ctx, int32_t T, const void* h, const int32_t*
                           const void* packed_w, void* y, void* stream);
 
 /*
+ * Expert plan with on-device redundancy (Section 6, "Load balance"). HOST function: every pointer
+ * is host memory, nothing touches the GPU. Spread M experts over N expert nodes, each with room
+ * for S expert copies (N*S >= M), so that the largest node cost
+ *     C_j = sum_i x[i][j] * max(a[i], K)        (x[i][j] = fraction of expert i served by node j)
+ * is small: a[i] = cost of computing expert i's active tokens over the last period, K = lowest
+ * cost a cold expert can have. The paper names a greedy approximation without detail; the steps
+ * taken are: (1) while spare slots remain, the expert with the largest per-copy share
+ * max(a[i], K) / replicas[i] gets one more copy (at most one per node), unless that share is already
+ * no more than the mean node cost; (2) the copies of an expert split it equally (x = 1 / replicas[i]);
+ * (3) copies, largest share first, go to the cheapest node that has a free slot and no copy of that
+ * expert. Ties go to the lower expert / copy / node index; arithmetic is IEEE double, left to right.
+ * In:  a[M], K.   Out: replicas[M]; slot_expert[N*S] and slot_copy[N*S] (node j owns entries
+ *      j*S .. j*S+S-1, filled in placement order, slot_expert = -1 for an empty slot); node_cost[N].
+ * MOE_ERR_INVALID_ARG for null pointers, sizes < 1, N*S < M or a NaN cost; MOE_ERR_UNSUPPORTED if
+ * the placement runs out of nodes that lack the expert (outputs are then unspecified).
+ */
+moe_status moe_plan_experts(int32_t M, int32_t N, int32_t S, const double* a, double K, int32_t* replicas,
+                            int32_t* slot_expert, int32_t* slot_copy, double* node_cost);
+
+/*
+ * Row ranges of expert copies (Section 6, "Load balance": a popular expert's tokens are shared
+ * between its copies). Copy r of the R = replicas[e] copies of expert e takes the r-th of R
+ * consecutive parts of expert e's rows in the expert-contiguous layout:
+ *     seg_begin[s] = offsets[e] + floor(r * c / R),  seg_end[s] = offsets[e] + floor((r + 1) * c / R),
+ *     e = slot_expert[s], r = slot_copy[s], c = offsets[e + 1] - offsets[e].
+ * In (device): slot_expert[n_slots], slot_copy[n_slots], replicas[E], offsets[E + 1]; n_slots <= 256.
+ * Out (device): seg_begin[n_slots], seg_end[n_slots]. A slot naming no expert in [0, E), or a copy
+ * number outside [0, R), gets the empty range [0, 0).
+ */
+moe_status moe_slot_segments(moe_ctx* ctx, int32_t n_slots, const int32_t* slot_expert, const int32_t* slot_copy,
+                             const int32_t* replicas, const int32_t* offsets, int32_t* seg_begin, int32_t* seg_end,
+                             void* stream);
+
+/*
+ * moe_expert_ffn over explicit row segments: what one expert node runs under an expert plan
+ * (Section 6, "Load balance"; the GEMMs are those of Section 4.2, Table 3). For every segment s and
+ * row r in [seg_begin[s], seg_end[s]), with e = seg_expert[s]:
+ *     h[r, :] = silu(xp[r, :] * W_gate_e^T) .* (xp[r, :] * W_up_e^T),   y[r, :] = h[r, :] * W_down_e^T
+ * Rows outside every segment are not touched. Each row's result is the same bits moe_expert_ffn
+ * gives that row, however the rows are cut into segments.
+ * In (device): xp[T*k, d], seg_begin / seg_end / seg_expert[n_segs] (n_segs <= 256), packed weights.
+ * T is the token count of the batch the rows come from: ranges are clipped to [0, T*k) and the
+ * segments must be disjoint (together they then hold at most T*k rows). rows_hint = expected rows in
+ * all segments together (only picks the tile shape; <= 0: T*k). A segment whose expert is outside
+ * [0, E) is skipped. Workspace h_ws[T*k, f]; out y[T*k, d].
+ */
+moe_status moe_expert_ffn_segments(moe_ctx* ctx, int32_t T, int32_t n_segs, int32_t rows_hint, const void* xp,
+                                   const int32_t* seg_begin, const int32_t* seg_end, const int32_t* seg_expert,
+                                   const void* packed_w, void* h_ws, void* y, void* stream);
+
+/*
  * Combine (Section 2.2: the layer output is the weighted sum of the selected experts' outputs):
  *     out[t, :] = sum_{j = 0..k-1} topk_w[t, j] * y[pos[t, j], :]     (float32 sum, j ascending)
  * In: y[A, d], pos[T, k], topk_w[T, k]. Out: out[T, d] in cfg.dtype.

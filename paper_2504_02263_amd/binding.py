@@ -24,7 +24,7 @@ _DTYPES = {"f32": (MOE_F32, torch.float32), "bf16": (MOE_BF16, torch.bfloat16)}
 
 EXPORTS = ("moe_create", "moe_destroy", "moe_last_error", "moe_status_string", "moe_packed_weight_bytes",
            "moe_pack_weights", "moe_route", "moe_gate_route", "moe_dispatch", "moe_expert_ffn", "moe_ffn_input", "moe_ffn_output",
-           "moe_combine")
+           "moe_combine", "moe_plan_experts", "moe_slot_segments", "moe_expert_ffn_segments")
 
 
 class MoeConfig(ctypes.Structure):
@@ -68,8 +68,12 @@ def load_library() -> ctypes.CDLL:
     lib.moe_ffn_input.argtypes = [vp, i32] + [vp] * 4 + [vp]
     lib.moe_ffn_output.argtypes = [vp, i32] + [vp] * 4 + [vp]
     lib.moe_combine.argtypes = [vp, i32] + [vp] * 4 + [vp]
+    dp, ip = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)
+    lib.moe_plan_experts.argtypes = [i32, i32, i32, dp, ctypes.c_double, ip, ip, ip, dp]
+    lib.moe_slot_segments.argtypes = [vp, i32] + [vp] * 6 + [vp]
+    lib.moe_expert_ffn_segments.argtypes = [vp, i32, i32, i32] + [vp] * 7 + [vp]
     for name in ("moe_pack_weights", "moe_route", "moe_gate_route", "moe_dispatch", "moe_expert_ffn", "moe_ffn_input", "moe_ffn_output",
-           "moe_combine"):
+           "moe_combine", "moe_plan_experts", "moe_slot_segments", "moe_expert_ffn_segments"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -155,6 +159,51 @@ def moe_combine(ctx, T, y, pos, topk_w, out, stream=None) -> None:
     _check(ctx, load_library().moe_combine(ctx, T, _ptr(y), _ptr(pos), _ptr(topk_w), _ptr(out), _stream(stream)))
 
 
+def moe_plan_experts(a, K: float, N: int, S: int):
+    """Host call (no GPU): returns (replicas[M], slots, node_cost[N]); slots[j] lists node j's
+    (expert, copy) pairs in placement order."""
+    M = len(a)
+    arr = (ctypes.c_double * M)(*[float(v) for v in a])
+    replicas = (ctypes.c_int32 * M)()
+    slot_expert = (ctypes.c_int32 * (N * S))()
+    slot_copy = (ctypes.c_int32 * (N * S))()
+    cost = (ctypes.c_double * N)()
+    lib = load_library()
+    status = lib.moe_plan_experts(M, N, S, arr, float(K), replicas, slot_expert, slot_copy, cost)
+    if status != MOE_OK:
+        raise MoeError(status, lib.moe_status_string(status).decode())
+    slots = [[(slot_expert[j * S + q], slot_copy[j * S + q]) for q in range(S) if slot_expert[j * S + q] >= 0]
+             for j in range(N)]
+    return list(replicas), slots, list(cost)
+
+
+def moe_slot_segments(ctx, n_slots, slot_expert, slot_copy, replicas, offsets, seg_begin, seg_end, stream=None) -> None:
+    _check(ctx, load_library().moe_slot_segments(ctx, n_slots, _ptr(slot_expert), _ptr(slot_copy), _ptr(replicas),
+                                                 _ptr(offsets), _ptr(seg_begin), _ptr(seg_end), _stream(stream)))
+
+
+def moe_expert_ffn_segments(ctx, T, n_segs, rows_hint, xp, seg_begin, seg_end, seg_expert, packed_w, h_ws, y,
+                            stream=None) -> None:
+    _check(ctx, load_library().moe_expert_ffn_segments(ctx, T, n_segs, rows_hint, _ptr(xp), _ptr(seg_begin),
+                                                       _ptr(seg_end), _ptr(seg_expert), _ptr(packed_w), _ptr(h_ws),
+                                                       _ptr(y), _stream(stream)))
+
+
+class NodeShare:
+    """One expert node's slots under an expert plan: device copies of its (expert, copy) list and
+    the row ranges moe_slot_segments derives from a batch's offsets."""
+
+    def __init__(self, node_slots, replicas, device):
+        i32 = torch.int32
+        self.n = len(node_slots)
+        n = max(self.n, 1)
+        self.slot_expert = torch.tensor([e for e, _ in node_slots] or [0], dtype=i32, device=device)
+        self.slot_copy = torch.tensor([r for _, r in node_slots] or [0], dtype=i32, device=device)
+        self.replicas = torch.tensor(list(replicas), dtype=i32, device=device)
+        self.seg_begin = torch.zeros(n, dtype=i32, device=device)
+        self.seg_end = torch.zeros(n, dtype=i32, device=device)
+
+
 class MoEPath:
     """Buffers for one (T_max, d, f, E, k, dtype) layer plus the four hot calls over them."""
 
@@ -220,6 +269,16 @@ class MoEPath:
 
     def combine(self, T, stream=None):
         moe_combine(self.ctx, T, self.y, self.pos, self.topk_w, self.out, stream)
+
+    def node_share(self, node_slots, replicas) -> NodeShare:
+        return NodeShare(node_slots, replicas, self.device)
+
+    def expert_ffn_node(self, T, share: NodeShare, rows_hint=0, stream=None):
+        """The expert FFN over one node's slots of an expert plan (after route and dispatch)."""
+        moe_slot_segments(self.ctx, share.n, share.slot_expert, share.slot_copy, share.replicas, self.offsets,
+                          share.seg_begin, share.seg_end, stream)
+        moe_expert_ffn_segments(self.ctx, T, share.n, rows_hint, self.xp, share.seg_begin, share.seg_end,
+                                share.slot_expert, self.packed, self.h, self.y, stream)
 
     def forward(self, x, logits, stream=None):
         """One pass of the whole hot path; returns out[:T] (a view of the preallocated buffer)."""

@@ -8,7 +8,10 @@
 // (gate, up) of one 32-column tile for the input GEMM, two neighbouring 32-column tiles for the
 // output GEMM. A wavefront streams its fragments from HBM straight into registers, 1 KiB fully
 // contiguous per load. Tokens (the other operand) are staged through LDS and shared by the
-// wavefronts of the workgroup. Per-expert row ranges come from `offsets` on the device.
+// wavefronts of the workgroup. Row ranges stay on the device: every kernel works on a list of
+// segments (rows [begin, end) to be multiplied with one expert's weights). For the plain layer
+// segment e is expert e's rows, begin = offsets, end = offsets + 1; with several copies of a
+// popular expert (Section 6, "Load balance") a copy is a segment holding part of that expert's rows.
 #include <math.h>
 #include <stdlib.h>
 #include <type_traits>
@@ -32,30 +35,38 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
+struct Segs {
+  const int32_t* begin;   // [count] first row of each segment
+  const int32_t* end;     // [count] one past its last row
+  const int32_t* expert;  // [count] whose weights the segment uses; nullptr: segment s uses expert s
+  int count;              // segments, <= 256
+  int experts;            // experts in the packed weights
+  int rows_cap;           // rows the activation buffers hold; ranges are clipped to it
+};
+
 struct TileLoc {
-  int expert;   // -1: this workgroup has no tile
+  int expert;   // segment index; -1: this workgroup has no tile
   int row0;     // first row of the m-tile
   int rows;     // rows of the m-tile (<= BM)
   int within;   // position inside the expert's block of `per_tile`-sized groups (see locate_tile)
   int tiles;    // m-tiles of this expert
 };
 
-// Work items are ordered expert-major: expert e owns tiles_e * per_tile consecutive positions,
+// Work items are ordered segment-major ("expert" below = segment): expert e owns tiles_e * per_tile consecutive positions,
 // tiles_e = ceil(c_e / BM). Position q inside an expert's block maps to m-tile q % tiles_e and
 // `within` = q / tiles_e, so the m-tiles that share one group of weight columns are neighbours.
 // BALANCED: the expert's rows are split evenly over its tiles in multiples of 32 rows (so
 // 1072 rows with BM = 256 become 224 + 224 + 224 + 224 + 176, not 4 x 256 + 48).
 // All threads of the workgroup (>= 256, one per expert) must call this.
 template <bool BALANCED>
-__device__ __forceinline__ TileLoc locate_tile(const int32_t* __restrict__ offsets, int E, int BM, int per_tile,
-                                               int pos) {
+__device__ __forceinline__ TileLoc locate_tile(const Segs& segs, int BM, int per_tile, int pos) {
   __shared__ int s_wave_total[8];
   __shared__ int s_loc[5];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   int lo = 0, hi = 0;
-  if (tid < E) {
-    lo = offsets[tid];
-    hi = offsets[tid + 1];
+  if (tid < segs.count) {
+    lo = max(0, min(segs.begin[tid], segs.rows_cap));
+    hi = max(lo, min(segs.end[tid], segs.rows_cap));
   }
   const int nt = (hi - lo + BM - 1) / BM;
   int incl = nt;
@@ -88,6 +99,12 @@ __device__ __forceinline__ TileLoc locate_tile(const int32_t* __restrict__ offse
   t.within = s_loc[3];
   t.tiles = s_loc[4];
   return t;
+}
+
+// Expert whose weights segment `seg` uses; -1 if the list names none of the packed experts.
+__device__ __forceinline__ int segment_expert(const Segs& segs, int seg) {
+  const int e = segs.expert ? segs.expert[seg] : seg;
+  return (unsigned)e < (unsigned)segs.experts ? e : -1;
 }
 
 __device__ __forceinline__ float silu(float g) { return g / (1.f + __expf(-g)); }
@@ -226,10 +243,9 @@ struct Gemm {
 };
 
 template <int MTW, int NW, int NST, int WN, int WM, bool GATEUP, bool NTL>
-__global__ __launch_bounds__(64 * WN * WM) void ffn_bf16_kernel(const u32x4* __restrict__ X,
-                                                               const int32_t* __restrict__ offsets,
+__global__ __launch_bounds__(64 * WN * WM) void ffn_bf16_kernel(const u32x4* __restrict__ X, const Segs segs,
                                                                const u32x4* __restrict__ Wp, __bf16* __restrict__ C,
-                                                               int E, int N, int K) {
+                                                               int N, int K) {
   static_assert(NST % 2 == 0, "chunk parity must equal ring-slot parity");
   static_assert(WN * WM >= 4, "the tile locator needs one thread per expert (256)");
   static_assert(NW == 2 || !GATEUP, "gate and up fragments are consumed together");
@@ -242,10 +258,11 @@ __global__ __launch_bounds__(64 * WN * WM) void ffn_bf16_kernel(const u32x4* __r
   const int groups = (units + WN - 1) / WN;
   const int groups_per_xcd = (groups + 7) / 8;
   const int xcd = blockIdx.x & 7;
-  const TileLoc loc = locate_tile<false>(offsets, E, BM, groups_per_xcd, blockIdx.x >> 3);
+  const TileLoc loc = locate_tile<false>(segs, BM, groups_per_xcd, blockIdx.x >> 3);
   if (loc.expert < 0) return;
   const int group = loc.within * 8 + ((xcd + loc.expert) & 7);  // rotate per expert: evens out a group count that is not a multiple of 8
-  if (group >= groups) return;
+  const int wexp = segment_expert(segs, loc.expert);
+  if (group >= groups || wexp < 0) return;
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int wn = w % WN, wm = w / WN;
@@ -260,7 +277,7 @@ __global__ __launch_bounds__(64 * WN * WM) void ffn_bf16_kernel(const u32x4* __r
   {
     const int u = has_n ? unit : 0;
     const int pair = NW == 2 ? u : u >> 1, sel = NW == 2 ? 0 : u & 1;
-    g.wbase = Wp + ((size_t)loc.expert * NP + pair) * KS * 128 + sel * 64 + lane;
+    g.wbase = Wp + ((size_t)wexp * NP + pair) * KS * 128 + sel * 64 + lane;
   }
   g.trow = tid >> 3;
   const int tunit = tid & 7;
@@ -477,23 +494,23 @@ __device__ __forceinline__ void wide_tile(const u32x4* __restrict__ X, const u32
 }
 
 template <bool GATEUP>
-__global__ __launch_bounds__(256) void ffn_bf16_wide_kernel(const u32x4* __restrict__ X,
-                                                           const int32_t* __restrict__ offsets,
-                                                           const u32x4* __restrict__ Wp, __bf16* __restrict__ C, int E,
+__global__ __launch_bounds__(256) void ffn_bf16_wide_kernel(const u32x4* __restrict__ X, const Segs segs,
+                                                           const u32x4* __restrict__ Wp, __bf16* __restrict__ C,
                                                            int N, int K) {
   __shared__ u32x4 slab[3 * kWideBM * 8];
   const int NP = GATEUP ? N / 32 : N / 64;
   const int groups = (NP + 3) / 4;
   const int groups_per_xcd = (groups + 7) / 8;
   const int xcd = blockIdx.x & 7;
-  const TileLoc loc = locate_tile<true>(offsets, E, kWideBM, groups_per_xcd, blockIdx.x >> 3);
+  const TileLoc loc = locate_tile<true>(segs, kWideBM, groups_per_xcd, blockIdx.x >> 3);
   if (loc.expert < 0) return;
   const int group = loc.within * 8 + ((xcd + loc.expert) & 7);  // rotate per expert: evens out a group count that is not a multiple of 8
-  if (group >= groups || loc.rows <= 0) return;
+  const int wexp = segment_expert(segs, loc.expert);
+  if (group >= groups || loc.rows <= 0 || wexp < 0) return;
   const int pair = group * 4 + (threadIdx.x >> 6);
   const bool has_n = pair < NP;
   const int rows = loc.rows;
-  const u32x4* wbase = Wp + ((size_t)loc.expert * NP + (has_n ? pair : 0)) * (K / 16) * 128 + (threadIdx.x & 63);
+  const u32x4* wbase = Wp + ((size_t)wexp * NP + (has_n ? pair : 0)) * (K / 16) * 128 + (threadIdx.x & 63);
   const int mu = __builtin_amdgcn_readfirstlane((rows + 31) / 32);  // live 32-row groups, 1..8
   // Tiles of up to 5 row groups have registers to spare for a deeper weight ring (K / 64 must divide
   // by it). An expert with a single m-tile reads its weights once: non-temporal loads, as in the
@@ -518,15 +535,17 @@ __global__ __launch_bounds__(256) void ffn_bf16_wide_kernel(const u32x4* __restr
 // f32 grouped GEMM, plain FMA: 32 (m) x 64 (n) tile per workgroup, K in chunks of 32 through LDS.
 // Thread (tx = tid % 64, ty = tid / 64) computes rows ty * 8 .. + 7 of column tx.
 template <int NW>
-__global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ X, const int32_t* __restrict__ offsets,
+__global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ X, const Segs segs,
                                                       const float* __restrict__ W0, const float* __restrict__ W1,
-                                                      float* __restrict__ C, int E, int N, int K) {
+                                                      float* __restrict__ C, int N, int K) {
   constexpr int BM = 32, BN = 64, BK = 32;
   __shared__ float xs[BM][BK + 1];
   __shared__ float ws[NW][BN][BK + 1];
 
-  const TileLoc loc = locate_tile<false>(offsets, E, BM, 1, blockIdx.y);
+  const TileLoc loc = locate_tile<false>(segs, BM, 1, blockIdx.y);
   if (loc.expert < 0) return;
+  const int wexp = segment_expert(segs, loc.expert);
+  if (wexp < 0) return;
   const int tid = threadIdx.x, tx = tid & 63, ty = tid >> 6;
   const int rows = loc.rows;
   const int n0 = blockIdx.x * BN;
@@ -548,7 +567,7 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ 
       const float* Wm = s == 0 ? W0 : W1;
       float4 a = {0.f, 0.f, 0.f, 0.f}, b = a;
       if (n0 + wr < N) {
-        const float* p = Wm + ((size_t)loc.expert * N + n0 + wr) * K + k0 + wc;
+        const float* p = Wm + ((size_t)wexp * N + n0 + wr) * K + k0 + wc;
         a = *reinterpret_cast<const float4*>(p);
         b = *reinterpret_cast<const float4*>(p + 4);
       }
@@ -583,31 +602,50 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ 
   }
 }
 
-// Upper bound on the m-tiles of all experts: sum_e ceil(c_e / BM) <= A / BM + min(E, A).
-inline int max_m_tiles(int A, int E, int BM) { return A / BM + (E < A ? E : A); }
+// Upper bound on the m-tiles of S segments holding at most A rows: sum ceil(c / BM) <= A / BM + min(S, A).
+inline int max_m_tiles(int A, int S, int BM) { return A / BM + (S < A ? S : A); }
 
 template <int MTW, int NW, int NST, int WN, int WM, bool GATEUP, bool NTL>
-void launch_bf16(const void* X, const int32_t* offsets, const void* Wp, void* C, int A, int E, int N, int K,
-                 hipStream_t stream) {
+void launch_bf16(const void* X, const Segs& segs, const void* Wp, void* C, int A, int N, int K, hipStream_t stream) {
   constexpr int BM = 32 * MTW * WM;
   const int NP = GATEUP ? N / 32 : N / 64;
   const int units = NW == 2 ? NP : 2 * NP;
   const int groups = (units + WN - 1) / WN;
   const int groups_per_xcd = (groups + 7) / 8;
-  const dim3 grid(8 * groups_per_xcd * max_m_tiles(A, E, BM)), block(64 * WN * WM);
+  const dim3 grid(8 * groups_per_xcd * max_m_tiles(A, segs.count, BM)), block(64 * WN * WM);
   hipLaunchKernelGGL((ffn_bf16_kernel<MTW, NW, NST, WN, WM, GATEUP, NTL>), grid, block, 0, stream,
-                     static_cast<const u32x4*>(X), offsets, static_cast<const u32x4*>(Wp), static_cast<__bf16*>(C), E,
-                     N, K);
+                     static_cast<const u32x4*>(X), segs, static_cast<const u32x4*>(Wp), static_cast<__bf16*>(C), N, K);
 }
 
 template <bool GATEUP>
-void launch_bf16_wide(const void* X, const int32_t* offsets, const void* Wp, void* C, int A, int E, int N, int K,
+void launch_bf16_wide(const void* X, const Segs& segs, const void* Wp, void* C, int A, int N, int K,
                       hipStream_t stream) {
   const int NP = GATEUP ? N / 32 : N / 64;
   const int groups_per_xcd = ((NP + 3) / 4 + 7) / 8;
-  const dim3 grid(8 * groups_per_xcd * max_m_tiles(A, E, kWideBM)), block(256);
-  hipLaunchKernelGGL((ffn_bf16_wide_kernel<GATEUP>), grid, block, 0, stream, static_cast<const u32x4*>(X), offsets,
-                     static_cast<const u32x4*>(Wp), static_cast<__bf16*>(C), E, N, K);
+  const dim3 grid(8 * groups_per_xcd * max_m_tiles(A, segs.count, kWideBM)), block(256);
+  hipLaunchKernelGGL((ffn_bf16_wide_kernel<GATEUP>), grid, block, 0, stream, static_cast<const u32x4*>(X), segs,
+                     static_cast<const u32x4*>(Wp), static_cast<__bf16*>(C), N, K);
+}
+
+// Copy r of R of expert e takes the r-th of R consecutive parts of [offsets[e], offsets[e + 1]).
+__global__ void slot_segments_kernel(const int32_t* __restrict__ slot_expert, const int32_t* __restrict__ slot_copy,
+                                     const int32_t* __restrict__ replicas, const int32_t* __restrict__ offsets,
+                                     int n_slots, int E, int32_t* __restrict__ seg_begin,
+                                     int32_t* __restrict__ seg_end) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= n_slots) return;
+  const int e = slot_expert[s];
+  int lo = 0, hi = 0;
+  if ((unsigned)e < (unsigned)E) {
+    const int R = replicas[e], r = slot_copy[s];
+    if (R >= 1 && r >= 0 && r < R) {
+      const long long base = offsets[e], c = offsets[e + 1] - base;
+      lo = (int)(base + (r * c) / R);
+      hi = (int)(base + ((r + 1) * c) / R);
+    }
+  }
+  seg_begin[s] = lo;
+  seg_end[s] = hi;
 }
 
 }  // namespace
@@ -635,18 +673,29 @@ hipError_t launch_pack_weights(const moe_config& cfg, const void* w_gate, const 
   return err;
 }
 
-hipError_t launch_ffn_stage(const moe_config& cfg, int stage, int T, const void* in, const int32_t* offsets,
-                            const void* packed, void* out, hipStream_t stream) {
-  const int A = T * cfg.k;
-  if (A == 0) return hipSuccess;
+hipError_t launch_slot_segments(const int32_t* slot_expert, const int32_t* slot_copy, const int32_t* replicas,
+                                const int32_t* offsets, int n_slots, int E, int32_t* seg_begin, int32_t* seg_end,
+                                hipStream_t stream) {
+  if (n_slots == 0) return hipSuccess;
+  hipLaunchKernelGGL(slot_segments_kernel, dim3((n_slots + 255) / 256), dim3(256), 0, stream, slot_expert, slot_copy,
+                     replicas, offsets, n_slots, E, seg_begin, seg_end);
+  return hipGetLastError();
+}
+
+hipError_t launch_ffn_segments(const moe_config& cfg, int stage, const int32_t* seg_begin, const int32_t* seg_end,
+                               const int32_t* seg_expert, int n_segs, int rows_bound, int rows_hint, int rows_cap,
+                               const void* in, const void* packed, void* out, hipStream_t stream) {
+  const int A = rows_bound;
+  if (A == 0 || n_segs == 0) return hipSuccess;
+  const Segs segs{seg_begin, seg_end, seg_expert, n_segs, cfg.E, rows_cap};
   const size_t one = (size_t)cfg.E * cfg.d * cfg.f;  // elements of one matrix set
   const int N = stage == 0 ? cfg.f : cfg.d, K = stage == 0 ? cfg.d : cfg.f;
   if (cfg.dtype == MOE_BF16) {
-    // The host never sees the per-expert counts, so the tile shape comes from the mean rows per
-    // expert: mean + 3 sqrt(mean) covers the spread of a near-uniform router, so most experts fit
-    // one m-tile. Up to 128 rows: 8 wavefronts side by side along N, weights streamed once
+    // The host never sees the per-segment row counts, so the tile shape comes from the mean rows
+    // per segment: mean + 3 sqrt(mean) covers the spread of a near-uniform router, so most experts
+    // fit one m-tile. Up to 128 rows: 8 wavefronts side by side along N, weights streamed once
     // (non-temporal). Above: the 256-row matrix-core-bound kernel, weights shared through L2.
-    const float mean = (float)A / cfg.E;
+    const float mean = (float)rows_hint / n_segs;
     const float want = mean + 3.f * sqrtf(mean);
     // Tuning knob (read once): MOE_FFN_WIDE_ABOVE=<rows> moves the switch-over between the two kernels.
     static const float wide_above = [] {
@@ -655,27 +704,34 @@ hipError_t launch_ffn_stage(const moe_config& cfg, int stage, int T, const void*
     }();
     const char* w = static_cast<const char*>(packed) + (stage == 0 ? 0 : 2 * one * 2);
     if (stage == 0) {
-      if (want <= 32.f) launch_bf16<1, 2, 2, 8, 1, true, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
-      else if (want <= 64.f) launch_bf16<2, 2, 2, 8, 1, true, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
-      else if (want <= 128.f || want <= wide_above) launch_bf16<4, 2, 2, 8, 1, true, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
-      else launch_bf16_wide<true>(in, offsets, w, out, A, cfg.E, N, K, stream);
+      if (want <= 32.f) launch_bf16<1, 2, 2, 8, 1, true, true>(in, segs, w, out, A, N, K, stream);
+      else if (want <= 64.f) launch_bf16<2, 2, 2, 8, 1, true, true>(in, segs, w, out, A, N, K, stream);
+      else if (want <= 128.f || want <= wide_above) launch_bf16<4, 2, 2, 8, 1, true, true>(in, segs, w, out, A, N, K, stream);
+      else launch_bf16_wide<true>(in, segs, w, out, A, N, K, stream);
     } else {
-      if (want <= 32.f) launch_bf16<1, 1, 2, 8, 1, false, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
-      else if (want <= 64.f) launch_bf16<2, 1, 2, 8, 1, false, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
-      else if (want <= 128.f || want <= wide_above) launch_bf16<4, 1, 2, 8, 1, false, true>(in, offsets, w, out, A, cfg.E, N, K, stream);
-      else launch_bf16_wide<false>(in, offsets, w, out, A, cfg.E, N, K, stream);
+      if (want <= 32.f) launch_bf16<1, 1, 2, 8, 1, false, true>(in, segs, w, out, A, N, K, stream);
+      else if (want <= 64.f) launch_bf16<2, 1, 2, 8, 1, false, true>(in, segs, w, out, A, N, K, stream);
+      else if (want <= 128.f || want <= wide_above) launch_bf16<4, 1, 2, 8, 1, false, true>(in, segs, w, out, A, N, K, stream);
+      else launch_bf16_wide<false>(in, segs, w, out, A, N, K, stream);
     }
     return hipGetLastError();
   }
   const float* wp = static_cast<const float*>(packed);
-  const dim3 grid((N + 63) / 64, max_m_tiles(A, cfg.E, 32));
+  const dim3 grid((N + 63) / 64, max_m_tiles(A, n_segs, 32));
   if (stage == 0)
-    hipLaunchKernelGGL((ffn_f32_kernel<2>), grid, dim3(256), 0, stream, static_cast<const float*>(in), offsets, wp,
-                       wp + one, static_cast<float*>(out), cfg.E, N, K);
+    hipLaunchKernelGGL((ffn_f32_kernel<2>), grid, dim3(256), 0, stream, static_cast<const float*>(in), segs, wp,
+                       wp + one, static_cast<float*>(out), N, K);
   else
-    hipLaunchKernelGGL((ffn_f32_kernel<1>), grid, dim3(256), 0, stream, static_cast<const float*>(in), offsets,
-                       wp + 2 * one, wp + 2 * one, static_cast<float*>(out), cfg.E, N, K);
+    hipLaunchKernelGGL((ffn_f32_kernel<1>), grid, dim3(256), 0, stream, static_cast<const float*>(in), segs,
+                       wp + 2 * one, wp + 2 * one, static_cast<float*>(out), N, K);
   return hipGetLastError();
+}
+
+// The plain layer: segment e = expert e's rows, offsets[e] .. offsets[e + 1].
+hipError_t launch_ffn_stage(const moe_config& cfg, int stage, int T, const void* in, const int32_t* offsets,
+                            const void* packed, void* out, hipStream_t stream) {
+  const int A = T * cfg.k;
+  return launch_ffn_segments(cfg, stage, offsets, offsets + 1, nullptr, cfg.E, A, A, A, in, packed, out, stream);
 }
 
 }  // namespace moe

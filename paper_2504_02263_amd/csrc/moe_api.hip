@@ -162,6 +162,38 @@ moe_status moe_expert_ffn(moe_ctx* ctx, int32_t T, const void* xp, const int32_t
   return finish(ctx, "moe_expert_ffn", err);
 }
 
+moe_status moe_slot_segments(moe_ctx* ctx, int32_t n_slots, const int32_t* slot_expert, const int32_t* slot_copy,
+                             const int32_t* replicas, const int32_t* offsets, int32_t* seg_begin, int32_t* seg_end,
+                             void* stream) {
+  const void* ptrs[] = {slot_expert, slot_copy, replicas, offsets, seg_begin, seg_end};
+  const moe_status s = check_call(ctx, "moe_slot_segments", 0, ptrs, 6);
+  if (s != MOE_OK) return s;
+  if (n_slots < 0 || n_slots > moe::kMaxExperts)
+    return fail(ctx, MOE_ERR_INVALID_ARG, "moe_slot_segments: n_slots = %d outside [0, %d]", n_slots, moe::kMaxExperts);
+  return finish(ctx, "moe_slot_segments",
+                moe::launch_slot_segments(slot_expert, slot_copy, replicas, offsets, n_slots, ctx->cfg.E, seg_begin,
+                                          seg_end, static_cast<hipStream_t>(stream)));
+}
+
+moe_status moe_expert_ffn_segments(moe_ctx* ctx, int32_t T, int32_t n_segs, int32_t rows_hint, const void* xp,
+                                   const int32_t* seg_begin, const int32_t* seg_end, const int32_t* seg_expert,
+                                   const void* packed_w, void* h_ws, void* y, void* stream) {
+  const void* ptrs[] = {xp, seg_begin, seg_end, seg_expert, packed_w, h_ws, y};
+  const moe_status s = check_call(ctx, "moe_expert_ffn_segments", T, ptrs, 7);
+  if (s != MOE_OK) return s;
+  if (n_segs < 0 || n_segs > moe::kMaxExperts)
+    return fail(ctx, MOE_ERR_INVALID_ARG, "moe_expert_ffn_segments: n_segs = %d outside [0, %d]", n_segs,
+                moe::kMaxExperts);
+  const int A = T * ctx->cfg.k;
+  const int hint = rows_hint > 0 ? (rows_hint < A ? rows_hint : A) : A;
+  hipError_t err = moe::launch_ffn_segments(ctx->cfg, 0, seg_begin, seg_end, seg_expert, n_segs, A, hint, A, xp,
+                                            packed_w, h_ws, static_cast<hipStream_t>(stream));
+  if (err == hipSuccess)
+    err = moe::launch_ffn_segments(ctx->cfg, 1, seg_begin, seg_end, seg_expert, n_segs, A, hint, A, h_ws, packed_w, y,
+                                   static_cast<hipStream_t>(stream));
+  return finish(ctx, "moe_expert_ffn_segments", err);
+}
+
 moe_status moe_combine(moe_ctx* ctx, int32_t T, const void* y, const int32_t* pos, const float* topk_w, void* out,
                        void* stream) {
   const void* ptrs[] = {y, pos, topk_w, out};

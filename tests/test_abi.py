@@ -73,6 +73,14 @@ def test_hot_calls_reject_bad_arguments_before_launch():
         assert b"aligned" in lib.moe_last_error(ctx)
         assert lib.moe_expert_ffn(ctx, 4, good, good, None, good, good, None) == B.MOE_ERR_INVALID_ARG
         assert lib.moe_pack_weights(ctx, good, good, good, None, None) == B.MOE_ERR_INVALID_ARG
+        # segment calls: slot / segment count outside [0, 256], null list, T out of range
+        assert lib.moe_slot_segments(ctx, 257, good, good, good, good, good, good, None) == B.MOE_ERR_INVALID_ARG
+        assert b"n_slots" in lib.moe_last_error(ctx)
+        assert lib.moe_slot_segments(ctx, 4, good, None, good, good, good, good, None) == B.MOE_ERR_INVALID_ARG
+        assert lib.moe_expert_ffn_segments(ctx, 4, -1, 0, good, good, good, good, good, good, good, None) == B.MOE_ERR_INVALID_ARG
+        assert b"n_segs" in lib.moe_last_error(ctx)
+        assert lib.moe_expert_ffn_segments(ctx, 65, 2, 0, good, good, good, good, good, good, good, None) == B.MOE_ERR_INVALID_ARG
+        assert lib.moe_expert_ffn_segments(ctx, 4, 2, 0, good, good, good, None, good, good, good, None) == B.MOE_ERR_INVALID_ARG
         # null context
         assert lib.moe_route(None, 4, good, good, good, good, good, None) == B.MOE_ERR_INVALID_ARG
     finally:
