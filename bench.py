@@ -140,6 +140,69 @@ def time_workload(cfg, paths, x_d, logits_d, steps, warmup, torch, R, synth):
                 step_flops=step_flops, step_min_bytes=step_min_bytes, serial_ms=serial_ms)
 
 
+def expert_plan_experiment(cfg, path, x_d, logits_d, N, S, B, torch, reps=10):
+    """Hot-expert redundancy on this workload (the paper's "Load balance" paragraph): every expert
+    node is one GPU, so each node's share of the expert FFN is timed alone on this GPU, for the
+    plain deployment (E / N consecutive experts per node, no copies) and for the greedy plan with
+    S slots per node. The per-expert loads are this batch's own counts (the paper plans from the
+    traffic of a previous period). Costs a_i and the cold floor K come from two timed single-expert
+    runs on this GPU: a small one (weight streaming) and a large one (per-row slope)."""
+    T, E, k = cfg.T, cfg.E, cfg.k
+    A = T * k
+    path.route(logits_d, T)
+    path.dispatch(x_d, T)
+    torch.cuda.synchronize()
+    counts = path.counts.cpu().tolist()
+    i32 = torch.int32
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    def one_expert(rows):
+        b = torch.zeros(1, dtype=i32, device="cuda")
+        e = torch.full((1,), rows, dtype=i32, device="cuda")
+        ex = torch.zeros(1, dtype=i32, device="cuda")
+        return timed(lambda: B.moe_expert_ffn_segments(path.ctx, T, 1, rows, path.xp, b, e, ex, path.packed, path.h, path.y))
+
+    big = min(A, 2048)
+    K_ms = one_expert(min(A, 16))
+    per_row_ms = (one_expert(big) - one_expert(big // 2)) / (big - big // 2)   # slope where rows, not weights, cost time
+    a = [c * per_row_ms for c in counts]
+
+    def measure(replicas, slots):
+        times, rows = [], []
+        for node in slots:
+            share = path.node_share(node, replicas)
+            hint = int(sum(counts[e] / replicas[e] for e, _ in node))
+            times.append(timed(lambda: path.expert_ffn_node(T, share, rows_hint=hint)))
+            rows.append(hint)
+        return times, rows
+
+    per = E // N
+    plain_slots = [[(e, 0) for e in range(j * per, (j + 1) * per if j < N - 1 else E)] for j in range(N)]
+    plain_cost = [sum(max(a[e], K_ms) for e, _ in node) for node in plain_slots]
+    plain_t, plain_rows = measure([1] * E, plain_slots)
+    replicas, slots, cost = B.moe_plan_experts(a, K_ms, N, S)
+    plan_t, plan_rows = measure(replicas, slots)
+    r3 = lambda v: [round(x, 4) for x in v]
+    return {"expert_plan": f"{cfg.name}: {E} experts on {N} nodes", "counts": counts,
+            "cost_model_ms": {"K_cold_floor": round(K_ms, 4), "per_row": round(per_row_ms, 6)},
+            "plain": {"slots_per_node": per, "rows": plain_rows, "predicted_ms": r3(plain_cost), "measured_ms": r3(plain_t),
+                      "max_ms": round(max(plain_t), 4), "max_over_mean": round(max(plain_t) / (sum(plain_t) / N), 3)},
+            "greedy": {"slots_per_node": S, "replicas": replicas, "slots": slots, "rows": plan_rows,
+                       "predicted_ms": r3(cost), "measured_ms": r3(plan_t), "max_ms": round(max(plan_t), 4),
+                       "max_over_mean": round(max(plan_t) / (sum(plan_t) / N), 3)},
+            "max_node_time_ratio_greedy_over_plain": round(max(plan_t) / max(plain_t), 3)}
+
+
 def roofline_entry(cfg, cost, ffn_in_ms, R):
     t = ffn_in_ms * 1e-3
     if cfg.dtype == "bf16":
@@ -221,6 +284,9 @@ def main():
                     help="override the workload's micro-batch count m (m > 1: two alternating streams)")
     ap.add_argument("--fit", action="store_true",
                     help="with --sweep: fit the paper's expert-time model T_e = k3*b_e + k4 to the measured FFN times")
+    ap.add_argument("--expert-plan", default="", metavar="N,S",
+                    help="also time every node's share of the expert FFN for N expert nodes, plain deployment "
+                         "against the greedy plan with S slots per node (hot experts get copies)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=256)
     ap.add_argument("--calibrate", action="store_true",
@@ -257,10 +323,11 @@ def main():
 
     if args.workload in synth.CONFIGS:
         cfg = synth.CONFIGS[args.workload]
-    elif args.workload.startswith("mixtral_T"):
-        cfg = synth.mixtral_sweep_config(int(args.workload[len("mixtral_T"):]))
+    elif "_T" in args.workload and any(n.startswith(args.workload.split("_T")[0] + "_T") for n in synth.CONFIGS):
+        base, T = args.workload.split("_T")          # a named shape at another token count, e.g. mixtral_T1024
+        cfg = next(c for n, c in synth.CONFIGS.items() if n.startswith(base + "_T")).with_T(int(T))
     else:
-        raise SystemExit(f"unknown workload {args.workload!r}; known: {sorted(synth.CONFIGS)} and mixtral_T<N>")
+        raise SystemExit(f"unknown workload {args.workload!r}; known: {sorted(synth.CONFIGS)}, or one of these shapes at another token count (<shape>_T<N>)")
 
     if args.micro_batches > 0:
         from dataclasses import replace
@@ -300,6 +367,13 @@ def main():
         fit = R.fit_expert_time([p[0] for p in pts], [p[1] for p in pts], split=128)
         fit["roofline_ridge_b"] = R.ridge_batch(R.MI355X_BF16_DENSE_FLOPS, R.MI355X_HBM_BYTES_PER_S)
         print(json.dumps({"expert_time_model": "T_e[ms] = k3*b_e + k4", "points": pts, "fit": fit}), flush=True)
+    if args.expert_plan:
+        N, S = (int(v) for v in args.expert_plan.split(","))
+        if cfg.E % N or N * S < cfg.E:
+            raise SystemExit("--expert-plan N,S needs E divisible by N and N*S >= E")
+        x, logits = make_inputs(cfg, args.seed, synth)
+        print(json.dumps(expert_plan_experiment(cfg, paths[0], dev(x, torch), dev(logits, torch), N, S, B, torch)),
+              flush=True)
     print(json.dumps(lines[-1]), flush=True)
     for p in paths:
         p.close()

@@ -9,6 +9,7 @@ import pytest
 import torch
 
 from oracle import moe_oracle as O
+from oracle import plan_oracle as P
 from paper_2504_02263_amd import binding as B
 from workloads import synth
 
@@ -90,6 +91,30 @@ def test_dbrx_zipf_sampled():
     layer = Layer(cfg, T_max=cfg.T)
     counts = layer.check(cfg, sample=48)
     assert counts.max() >= 2 * counts.mean()            # the Zipf bias really skews the load
+    # The same layer run node by node under the expert plan bench.py times (8 nodes, 3 slots each):
+    # the hot experts get copies, and no bit of any row changes (check() above tied those rows to the oracle).
+    p, A = layer.path, cfg.T * cfg.k
+    y_plain, h_plain = p.y[:A].clone(), p.h[:A].clone()
+    a = [float(c) for c in counts]
+    ref = P.plan_experts(a, float(counts.mean()) / 4, 8, 3)
+    replicas, slots, _ = B.moe_plan_experts(a, float(counts.mean()) / 4, 8, 3)
+    assert replicas == ref["replicas"] and slots == ref["slots"] and max(replicas) > 1
+    p.y.zero_()
+    p.h.zero_()
+    for node in slots:
+        share = p.node_share(node, replicas)
+        p.expert_ffn_node(cfg.T, share, rows_hint=A // 8)
+        b, e, _ = P.slot_segments(host(p.offsets), replicas, node)
+        assert host(share.seg_begin)[:len(node)].tolist() == b and host(share.seg_end)[:len(node)].tolist() == e
+    torch.cuda.synchronize()
+    assert torch.equal(p.y[:A], y_plain) and torch.equal(p.h[:A], h_plain)
+    layer.close()
+
+
+def test_scaled_moe_sampled():
+    cfg = synth.CONFIGS["scaled_moe_T2048"]
+    layer = Layer(cfg, T_max=cfg.T)
+    layer.check(cfg, sample=32)
     layer.close()
 
 

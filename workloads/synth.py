@@ -61,6 +61,10 @@ CONFIGS: Dict[str, LayerConfig] = {
     # fine-grained many-expert layer, 3 micro-batches
     "finegrained_T8192": LayerConfig("finegrained_T8192", T=8192, d=4096, f=1408, E=64, k=6, dtype="bf16",
                                      router="logits", micro_batches=3),
+    # the paper's third evaluation model (Section 7, model table: Scaled-MoE), as a decode micro-batch with
+    # 256 tokens per expert on average; an extra benchmark row, near-uniform load
+    "scaled_moe_T2048": LayerConfig("scaled_moe_T2048", T=2048, d=8192, f=8192, E=32, k=4, dtype="bf16",
+                                    router="logits"),
 }
 
 MIXTRAL_SWEEP_T: Tuple[int, ...] = (32, 64, 128, 256, 512, 1024, 2048, 4096)
