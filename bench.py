@@ -1,8 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the MoE hot path on one MI355X.
 
-A step is one pass of the whole path (moe_route -> moe_dispatch -> moe_ffn_input -> moe_ffn_output
--> moe_combine) over one batch of seeded synthetic input that is already resident in HBM. The
+A step is one pass of the whole path (moe_route_dispatch [= moe_route, moe_dispatch] -> moe_ffn_input
+-> moe_ffn_output -> moe_combine) over one batch of seeded synthetic input that is already resident in HBM. The
 default workload is the Mixtral-8x22B-shaped decode micro-batch (d=6144, f=16384, E=8, top-2,
 bf16, T=256), the configuration the headline metric is quoted on.
 
@@ -71,8 +71,7 @@ def time_workload(cfg, paths, x_d, logits_d, steps, warmup, torch, R, synth):
             j = 0 if serial else i % len(streams)
             path, stream = paths[j], streams[j]
             T = b - a
-            path.route(logits_d[a:b], T, stream)
-            path.dispatch(x_d[a:b], T, stream)
+            path.route_dispatch(x_d[a:b], logits_d[a:b], T, stream)   # = moe_route then moe_dispatch
             if ev is not None:
                 ev[i][0].record(stream)
             path.ffn_input(T, stream)
@@ -112,8 +111,9 @@ def time_workload(cfg, paths, x_d, logits_d, steps, warmup, torch, R, synth):
     # per-call breakdown on the first micro-batch (separate, untimed pass)
     a, b = ranges[0]
     T, path, stream = b - a, paths[0], streams[0]
-    names = ["route", "dispatch", "ffn_input", "ffn_output", "combine"]
+    names = ["route", "dispatch", "route_dispatch", "ffn_input", "ffn_output", "combine"]
     calls = [lambda: path.route(logits_d[a:b], T, stream), lambda: path.dispatch(x_d[a:b], T, stream),
+             lambda: path.route_dispatch(x_d[a:b], logits_d[a:b], T, stream),
              lambda: path.ffn_input(T, stream), lambda: path.ffn_output(T, stream), lambda: path.combine(T, stream)]
     reps = max(5, min(steps, 20))
     acc = {n: [] for n in names}

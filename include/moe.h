@@ -118,6 +118,17 @@ moe_status moe_dispatch(moe_ctx* ctx, int32_t T, const void* x, const int32_t* t
                         const int32_t* offsets, void* xp, int32_t* pos, int32_t* src, void* stream);
 
 /*
+ * moe_route followed by moe_dispatch as one call (Section 6 "Fused kernels": the paper fuses the
+ * top-k, the per-expert counts, the normalised weights and the scatter because each is a small
+ * memory-bound step). Same arguments, same outputs bit for bit as the two calls. For decode-sized
+ * batches (T <= 512, T*k <= 2048 and T*E <= 8192) everything runs in a single launch; larger
+ * batches run the four kernels of the two calls.
+ */
+moe_status moe_route_dispatch(moe_ctx* ctx, int32_t T, const float* logits, const void* x, int32_t* topk_idx,
+                              float* topk_w, int32_t* counts, int32_t* offsets, void* xp, int32_t* pos, int32_t* src,
+                              void* stream);
+
+/*
  * Expert FFN as a grouped SwiGLU GEMM (Section 4.2, Table 3; tensor-parallel degree 1):
  * for every expert e and row r in [offsets[e], offsets[e+1]):
  *     h[r, :] = silu(xp[r, :] * W_gate_e^T) .* (xp[r, :] * W_up_e^T)      ("FFN Input", fused)

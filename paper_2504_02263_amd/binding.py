@@ -24,7 +24,7 @@ _DTYPES = {"f32": (MOE_F32, torch.float32), "bf16": (MOE_BF16, torch.bfloat16)}
 
 EXPORTS = ("moe_create", "moe_destroy", "moe_last_error", "moe_status_string", "moe_packed_weight_bytes",
            "moe_pack_weights", "moe_route", "moe_gate_route", "moe_dispatch", "moe_expert_ffn", "moe_ffn_input", "moe_ffn_output",
-           "moe_combine", "moe_plan_experts", "moe_slot_segments", "moe_expert_ffn_segments")
+           "moe_combine", "moe_plan_experts", "moe_slot_segments", "moe_expert_ffn_segments", "moe_route_dispatch")
 
 
 class MoeConfig(ctypes.Structure):
@@ -64,6 +64,7 @@ def load_library() -> ctypes.CDLL:
     lib.moe_route.argtypes = [vp, i32] + [vp] * 5 + [vp]
     lib.moe_gate_route.argtypes = [vp, i32] + [vp] * 7 + [vp]
     lib.moe_dispatch.argtypes = [vp, i32] + [vp] * 6 + [vp]
+    lib.moe_route_dispatch.argtypes = [vp, i32] + [vp] * 9 + [vp]
     lib.moe_expert_ffn.argtypes = [vp, i32] + [vp] * 5 + [vp]
     lib.moe_ffn_input.argtypes = [vp, i32] + [vp] * 4 + [vp]
     lib.moe_ffn_output.argtypes = [vp, i32] + [vp] * 4 + [vp]
@@ -73,7 +74,7 @@ def load_library() -> ctypes.CDLL:
     lib.moe_slot_segments.argtypes = [vp, i32] + [vp] * 6 + [vp]
     lib.moe_expert_ffn_segments.argtypes = [vp, i32, i32, i32] + [vp] * 7 + [vp]
     for name in ("moe_pack_weights", "moe_route", "moe_gate_route", "moe_dispatch", "moe_expert_ffn", "moe_ffn_input", "moe_ffn_output",
-           "moe_combine", "moe_plan_experts", "moe_slot_segments", "moe_expert_ffn_segments"):
+           "moe_combine", "moe_plan_experts", "moe_slot_segments", "moe_expert_ffn_segments", "moe_route_dispatch"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -140,6 +141,12 @@ def moe_gate_route(ctx, T, x, w_router, logits, topk_idx, topk_w, counts, offset
 def moe_dispatch(ctx, T, x, topk_idx, offsets, xp, pos, src, stream=None) -> None:
     _check(ctx, load_library().moe_dispatch(ctx, T, _ptr(x), _ptr(topk_idx), _ptr(offsets), _ptr(xp), _ptr(pos),
                                             _ptr(src), _stream(stream)))
+
+
+def moe_route_dispatch(ctx, T, logits, x, topk_idx, topk_w, counts, offsets, xp, pos, src, stream=None) -> None:
+    _check(ctx, load_library().moe_route_dispatch(ctx, T, _ptr(logits), _ptr(x), _ptr(topk_idx), _ptr(topk_w),
+                                                  _ptr(counts), _ptr(offsets), _ptr(xp), _ptr(pos), _ptr(src),
+                                                  _stream(stream)))
 
 
 def moe_expert_ffn(ctx, T, xp, offsets, packed_w, h_ws, y, stream=None) -> None:
@@ -258,6 +265,11 @@ class MoEPath:
         T = x.shape[0] if T is None else T
         moe_dispatch(self.ctx, T, x, self.topk_idx, self.offsets, self.xp, self.pos, self.src, stream)
 
+    def route_dispatch(self, x, logits, T=None, stream=None):
+        T = x.shape[0] if T is None else T
+        moe_route_dispatch(self.ctx, T, logits, x, self.topk_idx, self.topk_w, self.counts, self.offsets, self.xp,
+                           self.pos, self.src, stream)
+
     def expert_ffn(self, T, stream=None):
         moe_expert_ffn(self.ctx, T, self.xp, self.offsets, self.packed, self.h, self.y, stream)
 
@@ -283,8 +295,7 @@ class MoEPath:
     def forward(self, x, logits, stream=None):
         """One pass of the whole hot path; returns out[:T] (a view of the preallocated buffer)."""
         T = x.shape[0]
-        self.route(logits, T, stream)
-        self.dispatch(x, T, stream)
+        self.route_dispatch(x, logits, T, stream)
         self.expert_ffn(T, stream)
         self.combine(T, stream)
         return self.out[:T]

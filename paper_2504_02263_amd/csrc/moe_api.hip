@@ -133,6 +133,23 @@ moe_status moe_dispatch(moe_ctx* ctx, int32_t T, const void* x, const int32_t* t
                                      pos, src, static_cast<hipStream_t>(stream)));
 }
 
+moe_status moe_route_dispatch(moe_ctx* ctx, int32_t T, const float* logits, const void* x, int32_t* topk_idx,
+                              float* topk_w, int32_t* counts, int32_t* offsets, void* xp, int32_t* pos, int32_t* src,
+                              void* stream) {
+  const void* ptrs[] = {logits, x, topk_idx, topk_w, counts, offsets, xp, pos, src};
+  const moe_status s = check_call(ctx, "moe_route_dispatch", T, ptrs, 9);
+  if (s != MOE_OK) return s;
+  const moe_config& c = ctx->cfg;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (moe::launch_route_dispatch_fused(logits, x, T, c.E, c.k, c.d * elem_bytes(ctx), topk_idx, topk_w, counts, offsets,
+                                       xp, pos, src, st))
+    return finish(ctx, "moe_route_dispatch", hipGetLastError());
+  hipError_t err = moe::launch_route(logits, T, c.E, c.k, topk_idx, topk_w, counts, offsets, st);
+  if (err == hipSuccess)
+    err = moe::launch_dispatch(x, topk_idx, offsets, T, c.E, c.k, c.d * elem_bytes(ctx), xp, pos, src, st);
+  return finish(ctx, "moe_route_dispatch", err);
+}
+
 moe_status moe_ffn_input(moe_ctx* ctx, int32_t T, const void* xp, const int32_t* offsets, const void* packed_w, void* h,
                          void* stream) {
   const void* ptrs[] = {xp, offsets, packed_w, h};

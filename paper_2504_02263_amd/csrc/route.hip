@@ -266,6 +266,182 @@ __global__ __launch_bounds__(256) void gate_topk_wave_kernel(const void* __restr
   }
 }
 
+// Routing and dispatch pack in ONE launch for decode-sized batches (A = T*k <= kFusedMaxA): the
+// paper's fused kernel does top-k, per-expert counts, normalised weights and the scatter together
+// because each is a small memory-bound step whose launch costs as much as its work (Section 6,
+// "Fused kernels"). There is no grid-wide barrier, so every workgroup redoes the cheap integer part
+// for the whole batch in LDS (top-k of all T tokens, histogram, offsets, stable ranks: a few
+// microseconds) and then copies its own share of the rows; workgroup 0 alone writes the
+// routing results. Same outputs, bit for bit, as route_topk/route_count followed by
+// dispatch_rank/dispatch_copy.
+constexpr int kFusedMaxA = 2048;
+constexpr int kFusedMaxT = 512;
+constexpr int kFusedMaxLogits = 8192;  // T * E floats staged in LDS
+
+// EM > 0 (E <= EM = 8 or 16): one lane owns a token and scans its E logits in registers, no
+// cross-lane traffic; EM = 0: the L-lane group of topk_group. Both give the same picks and weights.
+template <int L, int EM>
+__global__ __launch_bounds__(256) void route_dispatch_small_kernel(
+    const float* __restrict__ logits, const uint4* __restrict__ x, int T, int E, int k, int row_vecs,
+    int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, int32_t* __restrict__ counts,
+    int32_t* __restrict__ offsets, uint4* __restrict__ xp, int32_t* __restrict__ pos, int32_t* __restrict__ src) {
+  __shared__ float s_logits[kFusedMaxLogits];  // the whole logits matrix: one round of independent loads
+  __shared__ int s_idx[kFusedMaxA];            // expert of assignment i = t * k + j
+  __shared__ int s_src[kFusedMaxA];            // assignment that owns row r
+  __shared__ int s_base[kMaxExperts];          // counts, then the next free row of each expert
+  __shared__ int s_in_wave[4][kMaxExperts];    // assignments of e in each wavefront of the current chunk
+  __shared__ int s_wave_total[4];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const bool writer = blockIdx.x == 0;
+  const int A = T * k;
+
+  // 1. top-k of every token (256 / L tokens per pass)
+#pragma unroll 8
+  for (int u = tid; u < T * E; u += 256) s_logits[u] = logits[u];
+  __syncthreads();
+  if constexpr (EM > 0) {
+    for (int t = tid; t < T; t += 256) {
+      float v[EM];
+#pragma unroll
+      for (int e = 0; e < EM; ++e) {
+        float q = e < E ? s_logits[t * E + e] : -INFINITY;
+        v[e] = q != q ? -INFINITY : q;  // NaN ranks as -inf
+      }
+      unsigned taken = 0;
+      float row_max = 0.f, sum = 0.f, p[EM];
+      int pick[EM];
+#pragma unroll
+      for (int j = 0; j < EM; ++j) {
+        if (j < k) {
+          float bv = -INFINITY;
+          int bi = -1;
+#pragma unroll
+          for (int e = 0; e < EM; ++e)  // ascending scan, strict >: equal logits keep the lower index
+            if (e < E && !((taken >> e) & 1u) && (bi < 0 || v[e] > bv)) {
+              bv = v[e];
+              bi = e;
+            }
+          taken |= 1u << bi;
+          if (j == 0) row_max = bv;
+          p[j] = expf(bv - row_max);
+          sum += p[j];
+          pick[j] = bi;
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < EM; ++j) {
+        if (j < k) {
+          s_idx[t * k + j] = pick[j];
+          if (writer) {
+            topk_idx[(size_t)t * k + j] = pick[j];
+            topk_w[(size_t)t * k + j] = p[j] / sum;
+          }
+        }
+      }
+    }
+  } else {
+    const int sl = tid % L;
+    for (int t0 = 0; t0 < T; t0 += 256 / L) {
+      const int t = t0 + tid / L;
+      const bool valid = t < T;
+      float v[kMaxPerLane];
+#pragma unroll
+      for (int i = 0; i < kMaxPerLane; ++i) {
+        const int e = sl + i * L;
+        float q = -INFINITY;
+        if (valid && e < E) {
+          q = s_logits[t * E + e];
+          if (q != q) q = -INFINITY;  // NaN ranks as -inf
+        }
+        v[i] = q;
+      }
+      int my_idx;
+      float my_w;
+      topk_group<L>(v, sl, E, k, my_idx, my_w);
+      if (valid && sl < k) {
+        s_idx[t * k + sl] = my_idx;
+        if (writer) {
+          topk_idx[(size_t)t * k + sl] = my_idx;
+          topk_w[(size_t)t * k + sl] = my_w;
+        }
+      }
+    }
+  }
+  s_base[tid] = 0;
+  __syncthreads();
+
+  // 2. counts and offsets (thread e owns expert e; E <= 256)
+  for (int i = tid; i < A; i += 256) atomicAdd(&s_base[s_idx[i]], 1);
+  __syncthreads();
+  const int cnt = s_base[tid];
+  int incl = cnt;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int o = __shfl_up(incl, off);
+    if (lane >= off) incl += o;
+  }
+  if (lane == 63) s_wave_total[w] = incl;
+  __syncthreads();
+  int first = incl - cnt;
+  for (int ww = 0; ww < w; ++ww) first += s_wave_total[ww];
+  if (writer && tid < E) {
+    counts[tid] = cnt;
+    offsets[tid] = first;
+    if (tid == E - 1) offsets[E] = first + cnt;
+  }
+  s_base[tid] = first;
+
+  // 3. stable ranks, 256 assignments at a time in ascending order
+  const unsigned long long below = (1ull << lane) - 1ull;
+  for (int c0 = 0; c0 < A; c0 += 256) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s_in_wave[i][tid] = 0;
+    __syncthreads();  // also orders s_base updates of the previous chunk before the reads below
+    const int i = c0 + tid;
+    const int e = i < A ? s_idx[i] : -1;
+    int rank = 0;
+    unsigned long long todo = __ballot(e >= 0);
+    while (todo) {  // peel one expert value per round: the one held by the lowest lane still waiting
+      const int leader = __ffsll((long long)todo) - 1;
+      const int le = __shfl(e, leader);
+      const unsigned long long same = __ballot(e == le);
+      if (e == le) {
+        rank = __popcll(same & below);
+        if (lane == leader) s_in_wave[w][le] = __popcll(same);
+      }
+      todo &= ~same;
+    }
+    __syncthreads();
+    if (e >= 0) {
+      int r = s_base[e] + rank;
+      for (int ww = 0; ww < w; ++ww) r += s_in_wave[ww][e];
+      s_src[r] = i;
+      if (writer) {
+        pos[i] = r;
+        src[r] = i;
+      }
+    }
+    __syncthreads();
+    s_base[tid] += s_in_wave[0][tid] + s_in_wave[1][tid] + s_in_wave[2][tid] + s_in_wave[3][tid];
+  }
+  __syncthreads();
+
+  // 4. this workgroup's share of the rows: one wavefront per row, 16 bytes per lane per step
+  for (int r = blockIdx.x * 4 + w; r < A; r += gridDim.x * 4) {
+    const uint4* in = x + (size_t)(s_src[r] / k) * row_vecs;
+    uint4* out = xp + (size_t)r * row_vecs;
+    int c = lane;
+    for (; c + 192 < row_vecs; c += 256) {  // four independent loads in flight per lane
+      const uint4 q0 = in[c], q1 = in[c + 64], q2 = in[c + 128], q3 = in[c + 192];
+      out[c] = q0;
+      out[c + 64] = q1;
+      out[c + 128] = q2;
+      out[c + 192] = q3;
+    }
+    for (; c < row_vecs; c += 64) out[c] = in[c];
+  }
+}
+
 // One workgroup: histogram of the A picks in LDS, then an exclusive scan over E <= 256 bins by
 // the first wavefront (4 bins per lane).
 __global__ __launch_bounds__(1024) void route_count_kernel(const int32_t* __restrict__ topk_idx, int A, int E,
@@ -326,6 +502,25 @@ hipError_t launch_route(const float* logits, int T, int E, int k, int32_t* topk_
   return hipGetLastError();
 }
 
+
+bool launch_route_dispatch_fused(const float* logits, const void* x, int T, int E, int k, int row_bytes,
+                                 int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* offsets, void* xp,
+                                 int32_t* pos, int32_t* src, hipStream_t stream) {
+  const int A = T * k;
+  if (T < 1 || T > kFusedMaxT || A > kFusedMaxA || T * E > kFusedMaxLogits) return false;
+  const int L = E <= 8 ? 8 : E <= 16 ? 16 : E <= 32 ? 32 : 64;
+  const dim3 grid((A + 3) / 4 < 256 ? (A + 3) / 4 : 256), block(256);
+  const uint4* xv = static_cast<const uint4*>(x);
+  uint4* xpv = static_cast<uint4*>(xp);
+  const int rv = row_bytes / 16;
+  switch (L) {
+    case 8: hipLaunchKernelGGL((route_dispatch_small_kernel<8, 8>), grid, block, 0, stream, logits, xv, T, E, k, rv, topk_idx, topk_w, counts, offsets, xpv, pos, src); break;
+    case 16: hipLaunchKernelGGL((route_dispatch_small_kernel<16, 16>), grid, block, 0, stream, logits, xv, T, E, k, rv, topk_idx, topk_w, counts, offsets, xpv, pos, src); break;
+    case 32: hipLaunchKernelGGL((route_dispatch_small_kernel<32, 0>), grid, block, 0, stream, logits, xv, T, E, k, rv, topk_idx, topk_w, counts, offsets, xpv, pos, src); break;
+    default: hipLaunchKernelGGL((route_dispatch_small_kernel<64, 0>), grid, block, 0, stream, logits, xv, T, E, k, rv, topk_idx, topk_w, counts, offsets, xpv, pos, src); break;
+  }
+  return true;
+}
 
 template <int TT, int EPT, int L>
 static void launch_gate_topk(bool bf16, hipStream_t stream, const void* x, const float* wr, int T, int d, int E, int k,

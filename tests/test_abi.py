@@ -81,6 +81,8 @@ def test_hot_calls_reject_bad_arguments_before_launch():
         assert b"n_segs" in lib.moe_last_error(ctx)
         assert lib.moe_expert_ffn_segments(ctx, 65, 2, 0, good, good, good, good, good, good, good, None) == B.MOE_ERR_INVALID_ARG
         assert lib.moe_expert_ffn_segments(ctx, 4, 2, 0, good, good, good, None, good, good, good, None) == B.MOE_ERR_INVALID_ARG
+        assert lib.moe_route_dispatch(ctx, 4, good, None, good, good, good, good, good, good, good, None) == B.MOE_ERR_INVALID_ARG
+        assert lib.moe_route_dispatch(ctx, 65, good, good, good, good, good, good, good, good, good, None) == B.MOE_ERR_INVALID_ARG
         # null context
         assert lib.moe_route(None, 4, good, good, good, good, good, None) == B.MOE_ERR_INVALID_ARG
     finally:

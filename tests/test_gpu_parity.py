@@ -330,3 +330,34 @@ def test_all_tokens_to_one_expert():
     check_integers(path, ref, cfg.T, cfg.k)
     assert rel_fro(host(path.out), ref["out"]) <= 1e-2
     path.close()
+
+
+@pytest.mark.parametrize("T,E,k,d,dtype", [(1, 8, 2, 256, "bf16"), (256, 8, 2, 512, "bf16"), (512, 8, 4, 128, "bf16"),
+                                           (513, 8, 2, 128, "bf16"), (300, 64, 6, 256, "bf16"), (32, 256, 64, 128, "f32"),
+                                           (341, 16, 4, 384, "f32"), (2000, 8, 2, 128, "bf16")])
+def test_route_dispatch_one_call_equals_the_two_calls(T, E, k, d, dtype):
+    """moe_route_dispatch (a single launch up to T = 512, T*k = 2048; the four kernels beyond) against the
+    oracle and against moe_route + moe_dispatch: integers and copied rows bit for bit, weights identical."""
+    cfg = small_cfg(T, d, 128, E, k, dtype)
+    x = synth.make_activations(cfg, 21)
+    logits = synth.make_logits(cfg, 21)
+    logits[::5, : min(E, 3)] = 0.5                                   # ties inside the top-k
+    idx, w, counts, offsets = O.route(logits, k)
+    xp, pos, src = O.dispatch(x, idx, offsets)
+    ref = dict(topk_idx=idx, topk_w=w, counts=counts, offsets=offsets, xp=xp, pos=pos, src=src)
+    a = B.MoEPath(T, d, 128, E, k, dtype)
+    b = B.MoEPath(T, d, 128, E, k, dtype)
+    xd, ld = dev(x), dev(logits)
+    for p in (a, b):
+        for t in (p.topk_idx, p.pos, p.src, p.counts, p.offsets):
+            t.fill_(-7)
+        p.xp.zero_()
+    a.route_dispatch(xd, ld)
+    b.route(ld)
+    b.dispatch(xd)
+    torch.cuda.synchronize()
+    check_integers(a, ref, T, k)
+    for name in ("topk_idx", "topk_w", "counts", "offsets", "xp", "pos", "src"):
+        assert torch.equal(getattr(a, name), getattr(b, name)), name
+    a.close()
+    b.close()
