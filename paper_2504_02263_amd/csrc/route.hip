@@ -2,6 +2,7 @@
 // offsets (paper Section 2.2 for the routing rule; Section 6 "Fused kernels" for the list of
 // by-products: token counts per expert and normalised token weights).
 #include <limits.h>
+#include <type_traits>
 #include "moe_internal.h"
 
 namespace moe {
@@ -199,6 +200,274 @@ __global__ __launch_bounds__(256) void gate_topk_kernel(const void* __restrict__
       topk_w[(size_t)(t0 + r) * k + sl] = my_w;
     }
   }
+}
+
+typedef __bf16 gate_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float gate_floatx16 __attribute__((ext_vector_type(16)));
+typedef unsigned int gate_u32x4 __attribute__((ext_vector_type(4)));
+
+template <int I, int N, typename F>
+__device__ __forceinline__ void gate_static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    gate_static_for<I + 1, N>(f);
+  }
+}
+
+// Common end of the matrix-core gating kernels: add the four wavefronts' partial logits in the fixed
+// order 0, 1, 2, 3 through LDS, write the logits if asked to, and run the top-k on the 32 x E tile.
+template <int NT>
+__device__ __forceinline__ void gate_finish(const gate_floatx16 (&acc)[NT], float (*lg)[33], int t0, int T, int E,
+                                            int k, int L, float* __restrict__ logits,
+                                            int32_t* __restrict__ topk_idx, float* __restrict__ topk_w) {
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int frow = lane & 31, fg = lane >> 5;
+  // acc[i][r]: expert 32 i + 8 (r / 4) + 4 (lane / 32) + r % 4, token lane % 32
+  for (int turn = 0; turn < 4; ++turn) {
+    if (w == turn) {
+#pragma unroll
+      for (int i = 0; i < NT; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float* p = &lg[32 * i + 8 * (r >> 2) + 4 * fg + (r & 3)][frow];
+          *p = turn == 0 ? acc[i][r] : *p + acc[i][r];
+        }
+    }
+    __syncthreads();
+  }
+  if (logits) {
+    for (int u = tid; u < 32 * E; u += 256) {
+      const int r = u / E, e = u % E;
+      if (t0 + r < T) logits[(size_t)(t0 + r) * E + e] = lg[e][r];
+    }
+  }
+  auto topk_rows = [&](auto L_) {
+    constexpr int LL = decltype(L_)::value;
+    const int sl = tid % LL;
+    for (int base = 0; base < 32; base += 256 / LL) {
+      const int r = base + tid / LL;
+      const bool valid = t0 + r < T;
+      float v[kMaxPerLane];
+#pragma unroll
+      for (int i = 0; i < kMaxPerLane; ++i) {
+        const int e = sl + i * LL;
+        float q = -INFINITY;
+        if (valid && e < E) {
+          q = lg[e][r];
+          if (q != q) q = -INFINITY;
+        }
+        v[i] = q;
+      }
+      int my_idx;
+      float my_w;
+      topk_group<LL>(v, sl, E, k, my_idx, my_w);
+      if (valid && sl < k) {
+        topk_idx[(size_t)(t0 + r) * k + sl] = my_idx;
+        topk_w[(size_t)(t0 + r) * k + sl] = my_w;
+      }
+    }
+  };
+  if (L == 8) topk_rows(std::integral_constant<int, 8>{});
+  else if (L == 16) topk_rows(std::integral_constant<int, 16>{});
+  else if (L == 32) topk_rows(std::integral_constant<int, 32>{});
+  else topk_rows(std::integral_constant<int, 64>{});
+}
+
+// Matrix-core gating for up to 64 experts (NT <= 2) without workgroup barriers in the main loop:
+// each of the 4 wavefronts owns a quarter of the hidden dimension and stages its own 32-column
+// chunks (token tile, and the w_router tile split into hi + lo bf16 terms as described below) in a
+// private LDS region, reads them back in operand order and issues the MFMAs; LDS operations of one
+// wavefront execute in order, so nothing but the data dependences has to be waited for, and loads,
+// conversion and MFMAs of neighbouring chunks overlap. Rows of a chunk are 64 bytes (4 units of
+// 16 B); unit index XOR ((row >> 2) & 3) keeps both the row-major stores and the operand-order
+// reads free of bank conflicts.
+template <int NT, int D>
+__global__ __launch_bounds__(256) void gate_topk_mfma_wave_kernel(const uint16_t* __restrict__ x,
+                                                                  const float* __restrict__ wr, int T, int d, int E,
+                                                                  int k, int L, float* __restrict__ logits,
+                                                                  int32_t* __restrict__ topk_idx,
+                                                                  float* __restrict__ topk_w) {
+  __shared__ gate_u32x4 xs[4][32 * 4];
+  __shared__ gate_u32x4 whi[4][NT * 32 * 4];
+  __shared__ gate_u32x4 wlo[4][NT * 32 * 4];
+  __shared__ float lg[NT * 32][33];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int frow = lane & 31, fg = lane >> 5;
+  const int t0 = blockIdx.x * 32;
+  const int kq = d >> 2;  // columns of this wavefront: [w kq, (w + 1) kq); a multiple of 32
+  // staging role: units lane and lane + 64 of a 32-row x 4-unit tile: row = u / 4, unit = u % 4
+  int sdst[2];
+  const uint16_t* xsrc[2];
+  const float* wsrc[NT][2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int u = lane + 64 * h, row = u >> 2, unit = u & 3;
+    sdst[h] = row * 4 + (unit ^ ((row >> 2) & 3));
+    xsrc[h] = x + (size_t)min(t0 + row, T - 1) * d + w * kq + 8 * unit;
+#pragma unroll
+    for (int q = 0; q < NT; ++q) wsrc[q][h] = wr + (size_t)min(32 * q + row, E - 1) * d + w * kq + 8 * unit;
+  }
+  int frd[2];  // this lane's fragment piece of k-step s of a chunk
+#pragma unroll
+  for (int s2 = 0; s2 < 2; ++s2) frd[s2] = frow * 4 + ((2 * s2 + fg) ^ ((frow >> 2) & 3));
+
+  gate_floatx16 acc[NT];
+#pragma unroll
+  for (int i = 0; i < NT; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+
+  gate_u32x4 xreg[D][2];
+  float4 wreg[D][NT][2][2];
+  auto fetch = [&](auto j_, int c) {
+    constexpr int j = decltype(j_)::value;
+    c = min(c, kq - 32);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      xreg[j][h] = *reinterpret_cast<const gate_u32x4*>(xsrc[h] + c);
+#pragma unroll
+      for (int q = 0; q < NT; ++q) {
+        wreg[j][q][h][0] = *reinterpret_cast<const float4*>(wsrc[q][h] + c);
+        wreg[j][q][h][1] = *reinterpret_cast<const float4*>(wsrc[q][h] + c + 4);
+      }
+    }
+  };
+  auto step = [&](auto j_, int c) {
+    constexpr int j = decltype(j_)::value;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      xs[w][sdst[h]] = xreg[j][h];
+#pragma unroll
+      for (int q = 0; q < NT; ++q) {
+        const float4 a0 = wreg[j][q][h][0], a1 = wreg[j][q][h][1];
+        const float a[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+        gate_bf16x8 hi, lo;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          hi[i] = (__bf16)a[i];
+          lo[i] = (__bf16)(a[i] - (float)hi[i]);
+        }
+        whi[w][q * 128 + sdst[h]] = __builtin_bit_cast(gate_u32x4, hi);
+        wlo[w][q * 128 + sdst[h]] = __builtin_bit_cast(gate_u32x4, lo);
+      }
+    }
+    fetch(j_, c + 32 * D);  // refill this ring slot (past the end: a harmless refetch of the last chunk)
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+      const gate_bf16x8 b = __builtin_bit_cast(gate_bf16x8, xs[w][frd[s2]]);
+#pragma unroll
+      for (int i = 0; i < NT; ++i)
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(gate_bf16x8, whi[w][i * 128 + frd[s2]]), b, acc[i], 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < NT; ++i)
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(gate_bf16x8, wlo[w][i * 128 + frd[s2]]), b, acc[i], 0, 0, 0);
+    }
+  };
+  gate_static_for<0, D>([&](auto j_) { fetch(j_, 32 * decltype(j_)::value); });
+  // kq / 32 is a multiple of D (the launcher picks D so), and no load sits under a branch: the loop
+  // body is one basic block and every wait counts exactly the loads issued after the one it needs
+  for (int c0 = 0; c0 < kq; c0 += 32 * D)
+    gate_static_for<0, D>([&](auto j_) { step(j_, c0 + 32 * decltype(j_)::value); });
+  __syncthreads();
+  gate_finish<NT>(acc, lg, t0, T, E, k, L, logits, topk_idx, topk_w);
+}
+
+// Gating GEMM on the matrix cores, for more than 16 experts and bf16 activations (same fusion as
+// above: the logits go straight into the top-k, Section 6 "Fused kernels"). A workgroup owns 32
+// tokens and walks the hidden dimension in chunks of 64 columns. Per chunk its 256 threads load
+// the token tile (32 x 64 bf16) and the w_router tile (32 NT x 64 float32) with row-contiguous
+// 16-byte loads, D chunks ahead in a register ring (a chunk is only four MFMAs per expert tile, so
+// one chunk of lead would leave the load latency exposed); the float32 gating weights are split into two bf16
+// terms, w = hi + lo with |w - hi - lo| <= 2^-18 |w|, and all three tiles go to LDS in the
+// swizzled [row][8 x 16 B] layout of the FFN kernels. Wavefront s then takes MFMA k-step s of the
+// chunk (v_mfma_f32_32x32x16_bf16: w_router tile = A operand, token tile = B operand) and issues
+// one MFMA per term and expert tile, so the logits keep float32-level accuracy (the activations
+// are bf16 already). The four partial sums are added in wavefront order 0, 1, 2, 3 through LDS (a
+// fixed order: the logits, and with them the routing, are reproducible), then the top-k runs on
+// the 32 x E logits in LDS.
+template <int NT, int D>  // NT = 32-expert tiles (E <= 32 NT); D = ring depth; L = lanes per token in the top-k
+__global__ __launch_bounds__(256) void gate_topk_mfma_kernel(const uint16_t* __restrict__ x,
+                                                             const float* __restrict__ wr, int T, int d, int E, int k,
+                                                             int L, float* __restrict__ logits,
+                                                             int32_t* __restrict__ topk_idx,
+                                                             float* __restrict__ topk_w) {
+  __shared__ gate_u32x4 xs[32 * 8];
+  __shared__ gate_u32x4 whi[NT * 32 * 8];
+  __shared__ gate_u32x4 wlo[NT * 32 * 8];
+  __shared__ float lg[NT * 32][33];  // [expert][token], padded
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int frow = lane & 31, fg = lane >> 5;
+  const int t0 = blockIdx.x * 32;
+  // staging role: 16-byte unit (tid % 8) of row tid / 8 (+ 32 q for the w_router tile)
+  const int srow = tid >> 3, sunit = tid & 7;
+  const int sdst = srow * 8 + (sunit ^ ((srow >> 1) & 7));  // (row + 32 q) keeps the same swizzle term
+  const uint16_t* xsrc = x + (size_t)min(t0 + srow, T - 1) * d + 8 * sunit;
+  const float* wsrc[NT];
+#pragma unroll
+  for (int q = 0; q < NT; ++q) wsrc[q] = wr + (size_t)min(32 * q + srow, E - 1) * d + 8 * sunit;
+  // MFMA role: fragment piece of k-step w
+  const int frd = frow * 8 + ((2 * w + fg) ^ ((frow >> 1) & 7));
+
+  gate_floatx16 acc[NT];
+#pragma unroll
+  for (int i = 0; i < NT; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+
+  gate_u32x4 xreg[D];
+  float4 wreg[D][NT][2];
+#pragma unroll
+  for (int j = 0; j < D; ++j) {
+    const int c = min(64 * j, d - 64);
+    xreg[j] = *reinterpret_cast<const gate_u32x4*>(xsrc + c);
+#pragma unroll
+    for (int q = 0; q < NT; ++q) {
+      wreg[j][q][0] = *reinterpret_cast<const float4*>(wsrc[q] + c);
+      wreg[j][q][1] = *reinterpret_cast<const float4*>(wsrc[q] + c + 4);
+    }
+  }
+  for (int c0 = 0; c0 < d; c0 += 64 * D) {
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+      const int c = c0 + 64 * j;
+      {  // d / 64 is a multiple of D (the launcher picks D so): no load sits under a branch
+        xs[sdst] = xreg[j];
+#pragma unroll
+        for (int q = 0; q < NT; ++q) {
+          const float a[8] = {wreg[j][q][0].x, wreg[j][q][0].y, wreg[j][q][0].z, wreg[j][q][0].w,
+                              wreg[j][q][1].x, wreg[j][q][1].y, wreg[j][q][1].z, wreg[j][q][1].w};
+          gate_bf16x8 hi, lo;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            hi[i] = (__bf16)a[i];
+            lo[i] = (__bf16)(a[i] - (float)hi[i]);
+          }
+          whi[q * 256 + sdst] = __builtin_bit_cast(gate_u32x4, hi);
+          wlo[q * 256 + sdst] = __builtin_bit_cast(gate_u32x4, lo);
+        }
+        {  // refill this ring slot with chunk c + 64 D (past the end: a harmless refetch of the last chunk)
+          const int cn = min(c + 64 * D, d - 64);
+          xreg[j] = *reinterpret_cast<const gate_u32x4*>(xsrc + cn);
+#pragma unroll
+          for (int q = 0; q < NT; ++q) {
+            wreg[j][q][0] = *reinterpret_cast<const float4*>(wsrc[q] + cn);
+            wreg[j][q][1] = *reinterpret_cast<const float4*>(wsrc[q] + cn + 4);
+          }
+        }
+        __syncthreads();
+        const gate_bf16x8 b = __builtin_bit_cast(gate_bf16x8, xs[frd]);
+#pragma unroll
+        for (int i = 0; i < NT; ++i)
+          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(gate_bf16x8, whi[i * 256 + frd]), b, acc[i], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < NT; ++i)
+          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(gate_bf16x8, wlo[i * 256 + frd]), b, acc[i], 0, 0, 0);
+        __syncthreads();
+      }
+    }
+  }
+
+  gate_finish<NT>(acc, lg, t0, T, E, k, L, logits, topk_idx, topk_w);
 }
 
 // The same fusion for few experts (E <= EM = 8 or 16), where the batch is too small to fill the
@@ -485,10 +754,18 @@ __global__ __launch_bounds__(1024) void route_count_kernel(const int32_t* __rest
 
 }  // namespace
 
+// Lanes that share one token in topk_group: the smallest group with at most kMaxPerLane experts per
+// lane and one lane per pick (fewer lanes per token = more tokens per wavefront pass).
+static int topk_lanes(int E, int k) {
+  int L = 8;
+  while (L < 64 && (E > kMaxPerLane * L || k > L)) L *= 2;
+  return L;
+}
+
 hipError_t launch_route(const float* logits, int T, int E, int k, int32_t* topk_idx, float* topk_w, int32_t* counts,
                         int32_t* offsets, hipStream_t stream) {
   if (T > 0) {
-    const int L = E <= 8 ? 8 : E <= 16 ? 16 : E <= 32 ? 32 : 64;
+    const int L = topk_lanes(E, k);
     const int tokens_per_block = 4 * (64 / L);
     const dim3 grid((T + tokens_per_block - 1) / tokens_per_block), block(256);
     switch (L) {
@@ -508,14 +785,16 @@ bool launch_route_dispatch_fused(const float* logits, const void* x, int T, int 
                                  int32_t* pos, int32_t* src, hipStream_t stream) {
   const int A = T * k;
   if (T < 1 || T > kFusedMaxT || A > kFusedMaxA || T * E > kFusedMaxLogits) return false;
-  const int L = E <= 8 ? 8 : E <= 16 ? 16 : E <= 32 ? 32 : 64;
+  const int L = E <= 8 ? -8 : E <= 16 ? -16 : topk_lanes(E, k);  // negative: the lane-per-token variant
   const dim3 grid((A + 3) / 4 < 256 ? (A + 3) / 4 : 256), block(256);
   const uint4* xv = static_cast<const uint4*>(x);
   uint4* xpv = static_cast<uint4*>(xp);
   const int rv = row_bytes / 16;
   switch (L) {
-    case 8: hipLaunchKernelGGL((route_dispatch_small_kernel<8, 8>), grid, block, 0, stream, logits, xv, T, E, k, rv, topk_idx, topk_w, counts, offsets, xpv, pos, src); break;
-    case 16: hipLaunchKernelGGL((route_dispatch_small_kernel<16, 16>), grid, block, 0, stream, logits, xv, T, E, k, rv, topk_idx, topk_w, counts, offsets, xpv, pos, src); break;
+    case -8: hipLaunchKernelGGL((route_dispatch_small_kernel<8, 8>), grid, block, 0, stream, logits, xv, T, E, k, rv, topk_idx, topk_w, counts, offsets, xpv, pos, src); break;
+    case -16: hipLaunchKernelGGL((route_dispatch_small_kernel<16, 16>), grid, block, 0, stream, logits, xv, T, E, k, rv, topk_idx, topk_w, counts, offsets, xpv, pos, src); break;
+    case 8: hipLaunchKernelGGL((route_dispatch_small_kernel<8, 0>), grid, block, 0, stream, logits, xv, T, E, k, rv, topk_idx, topk_w, counts, offsets, xpv, pos, src); break;
+    case 16: hipLaunchKernelGGL((route_dispatch_small_kernel<16, 0>), grid, block, 0, stream, logits, xv, T, E, k, rv, topk_idx, topk_w, counts, offsets, xpv, pos, src); break;
     case 32: hipLaunchKernelGGL((route_dispatch_small_kernel<32, 0>), grid, block, 0, stream, logits, xv, T, E, k, rv, topk_idx, topk_w, counts, offsets, xpv, pos, src); break;
     default: hipLaunchKernelGGL((route_dispatch_small_kernel<64, 0>), grid, block, 0, stream, logits, xv, T, E, k, rv, topk_idx, topk_w, counts, offsets, xpv, pos, src); break;
   }
@@ -546,7 +825,33 @@ hipError_t launch_gate_route(const void* x, const float* w_router, int T, int d,
       if (bf16) hipLaunchKernelGGL((gate_topk_wave_kernel<16, true>), wgrid, dim3(256), 0, stream, x, w_router, T, d, E, k, logits, topk_idx, topk_w);
       else hipLaunchKernelGGL((gate_topk_wave_kernel<16, false>), wgrid, dim3(256), 0, stream, x, w_router, T, d, E, k, logits, topk_idx, topk_w);
     }
-    // more experts: 16-token workgroups (16 expert groups of EPT) while E allows it
+    // more experts, bf16 activations: the gating GEMM runs on the matrix cores
+    else if (bf16) {
+      const dim3 mgrid((T + 31) / 32);
+      const uint16_t* xb = static_cast<const uint16_t*>(x);
+      const int L = topk_lanes(E, k);
+      // ring depth: must divide the chunk count (d / 128 per wavefront, d / 64 per workgroup)
+#define MOE_GATE_LAUNCH(KERNEL) hipLaunchKernelGGL(KERNEL, mgrid, dim3(256), 0, stream, xb, w_router, T, d, E, k, L, logits, topk_idx, topk_w)
+      if (E <= 64) {
+        const int D = d % 512 == 0 ? 4 : d % 256 == 0 ? 2 : 1;
+        if (E <= 32) {
+          if (D == 4) MOE_GATE_LAUNCH((gate_topk_mfma_wave_kernel<1, 4>));
+          else if (D == 2) MOE_GATE_LAUNCH((gate_topk_mfma_wave_kernel<1, 2>));
+          else MOE_GATE_LAUNCH((gate_topk_mfma_wave_kernel<1, 1>));
+        } else {
+          if (D == 4) MOE_GATE_LAUNCH((gate_topk_mfma_wave_kernel<2, 4>));
+          else if (D == 2) MOE_GATE_LAUNCH((gate_topk_mfma_wave_kernel<2, 2>));
+          else MOE_GATE_LAUNCH((gate_topk_mfma_wave_kernel<2, 1>));
+        }
+      } else if (E <= 128) {
+        if (d % 256 == 0) MOE_GATE_LAUNCH((gate_topk_mfma_kernel<4, 4>));
+        else MOE_GATE_LAUNCH((gate_topk_mfma_kernel<4, 2>));
+      } else {
+        MOE_GATE_LAUNCH((gate_topk_mfma_kernel<8, 2>));
+      }
+#undef MOE_GATE_LAUNCH
+    }
+    // more experts, float32 activations: 16-token workgroups (16 expert groups of EPT) while E allows it
     else if (E <= 32) launch_gate_topk<16, 2, 32>(bf16, stream, x, w_router, T, d, E, k, logits, topk_idx, topk_w);
     else if (E <= 64) launch_gate_topk<16, 4, 64>(bf16, stream, x, w_router, T, d, E, k, logits, topk_idx, topk_w);
     else if (E <= 128) launch_gate_topk<32, 16, 64>(bf16, stream, x, w_router, T, d, E, k, logits, topk_idx, topk_w);

@@ -237,7 +237,8 @@ def test_calls_run_on_the_given_stream():
 
 @pytest.mark.parametrize("T,d,E,k,dtype", [(64, 256, 8, 2, "f32"), (257, 384, 16, 4, "bf16"), (1000, 512, 64, 6, "bf16"),
                                            (70, 128, 100, 7, "bf16"), (33, 256, 256, 8, "f32"), (5, 128, 5, 3, "bf16"),
-                                           (256, 6144, 8, 2, "bf16")])
+                                           (256, 6144, 8, 2, "bf16"), (45, 256, 32, 4, "bf16"), (40, 128, 256, 8, "bf16"),
+                                           (333, 1024, 17, 5, "bf16"), (100, 384, 128, 64, "bf16")])
 def test_gate_route(T, d, E, k, dtype):
     """moe_gate_route: the gate scores against the oracle's float64 product, and the routing
     bit-exact against the oracle routed on the very logits the GPU produced."""
