@@ -95,7 +95,9 @@ def time_workload(cfg, paths, x_d, logits_d, steps, warmup, torch, R, synth):
     sync()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / steps
-    ffn_in_ms = float(np.mean([a.elapsed_time(b) for evs in events for a, b in evs]))
+    ffn_in_all = [a.elapsed_time(b) for evs in events for a, b in evs]
+    ffn_in_ms = float(np.mean(ffn_in_all))
+    ffn_in_pct = [float(np.percentile(ffn_in_all, q)) for q in (10, 50, 90)]
 
     serial_ms = None
     if m > 1:   # the same micro-batches back to back on one stream, for comparison
@@ -136,7 +138,7 @@ def time_workload(cfg, paths, x_d, logits_d, steps, warmup, torch, R, synth):
     step_flops = sum(R.layer_cost(q - p, cfg.d, cfg.f, cfg.E, cfg.k, s, active_experts=active).flops for p, q in ranges)
     step_min_bytes = sum(R.layer_cost(q - p, cfg.d, cfg.f, cfg.E, cfg.k, s, active_experts=active).layer_min_bytes
                          for p, q in ranges)
-    return dict(ms_per_step=ms_per_step, ffn_in_ms=ffn_in_ms, calls_ms=calls_ms, counts=counts, cost=launch_cost,
+    return dict(ms_per_step=ms_per_step, ffn_in_ms=ffn_in_ms, ffn_in_pct=ffn_in_pct, calls_ms=calls_ms, counts=counts, cost=launch_cost,
                 step_flops=step_flops, step_min_bytes=step_min_bytes, serial_ms=serial_ms)
 
 
@@ -203,6 +205,34 @@ def expert_plan_experiment(cfg, path, x_d, logits_d, N, S, B, torch, reps=10):
             "max_node_time_ratio_greedy_over_plain": round(max(plan_t) / max(plain_t), 3)}
 
 
+def measure_ceilings(path, B, torch, reps=5):
+    """What this chip reaches for the roofline's two denominators, measured beside the layer: a plain
+    streaming read of the packed weights, and matrix-core issue from registers with real weight bits as
+    operands (bf16 layers only)."""
+    sink = torch.zeros(16, dtype=torch.float32, device="cuda")
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e-3
+
+    nbytes = path.packed.numel()
+    got = B.moe_probe_stream_read(path.ctx, path.packed, nbytes, sink)
+    out = {"stream_read_GB/s": round(got / timed(lambda: B.moe_probe_stream_read(path.ctx, path.packed, nbytes, sink)) / 1e9, 1),
+           "stream_read_bytes": got}
+    if path.dtype == "bf16":
+        flops = B.moe_probe_mfma(path.ctx, path.packed, 2048, 1024, sink)
+        out["mfma_loop_TFLOP/s"] = round(flops / timed(lambda: B.moe_probe_mfma(path.ctx, path.packed, 2048, 1024, sink)) / 1e12, 1)
+        out["mfma_loop"] = "v_mfma_f32_32x32x16_bf16 from registers, 1 wave per SIMD, operands = packed weight bits"
+    return out
+
+
 def roofline_entry(cfg, cost, ffn_in_ms, R):
     t = ffn_in_ms * 1e-3
     if cfg.dtype == "bf16":
@@ -246,7 +276,21 @@ def cpu_baseline(cfg, seed, W, x, logits, oracle_mod, sample_tokens):
             "host_cpus": os.cpu_count()}
 
 
-def result_line(cfg, steps, warmup, r, R, cpu):
+def per_call_rates(cfg, r, R):
+    """Algorithmic GB/s (and TFLOP/s for the GEMMs) of every call of the first micro-batch, from the per-call times."""
+    c, ms = r["cost"], r["calls_ms"]
+    by = {"route": c.route_bytes, "dispatch": c.dispatch_bytes, "route_dispatch": c.route_bytes + c.dispatch_bytes,
+          "ffn_input": c.ffn_in_bytes, "ffn_output": c.ffn_out_bytes, "combine": c.combine_bytes}
+    fl = {"ffn_input": c.ffn_in_flops, "ffn_output": c.ffn_out_flops}
+    out = {}
+    for n, t in ms.items():
+        out[n] = {"GB/s": round(by[n] / (t * 1e-3) / 1e9, 1)}
+        if n in fl:
+            out[n]["TFLOP/s"] = round(fl[n] / (t * 1e-3) / 1e12, 1)
+    return out
+
+
+def result_line(cfg, steps, warmup, r, R, cpu, ceilings=None):
     ms_per_step, counts, cost = r["ms_per_step"], r["counts"], r["cost"]
     sec = ms_per_step * 1e-3
     line = {
@@ -257,7 +301,8 @@ def result_line(cfg, steps, warmup, r, R, cpu):
         "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "f": cfg.f, "E": cfg.E, "k": cfg.k,
                    "micro_batches": cfg.micro_batches,
                    "tokens_per_expert_mean": cfg.T * cfg.k / cfg.E / cfg.micro_batches,
-                   "tokens_per_expert_max": int(counts.max()), "tokens_per_expert_min": int(counts.min())},
+                   "tokens_per_expert_max": int(counts.max()), "tokens_per_expert_min": int(counts.min()),
+                   "tokens_per_expert": [int(c) for c in counts]},
         "roofline": roofline_entry(cfg, cost, r["ffn_in_ms"], R),
         "cpu_baseline": cpu,
         "layer": {"tflops": round(r["step_flops"] / sec / 1e12, 2),
@@ -265,8 +310,16 @@ def result_line(cfg, steps, warmup, r, R, cpu):
                   "hbm_frac_of_min_bytes": round(r["step_min_bytes"] / sec / R.MI355X_HBM_BYTES_PER_S, 4),
                   "mfma_frac": round(r["step_flops"] / sec / R.MI355X_BF16_DENSE_FLOPS, 4)
                   if cfg.dtype == "bf16" else None,
-                  "calls_ms": {k: round(v, 5) for k, v in r["calls_ms"].items()}},
+                  "calls_ms": {k: round(v, 5) for k, v in r["calls_ms"].items()},
+                  "calls_rates": per_call_rates(cfg, r, R)},
     }
+    line["roofline"]["launch_ms_p10_p50_p90"] = [round(v, 5) for v in r["ffn_in_pct"]]
+    if ceilings:
+        line["ceilings"] = ceilings
+        rf = line["roofline"]
+        key = "stream_read_GB/s" if rf["bound"] == "hbm" else "mfma_loop_TFLOP/s"
+        if ceilings.get(key):
+            rf["frac_of_measured_ceiling"] = round(rf["achieved"] / ceilings[key], 4)
     if r["serial_ms"] is not None:
         line["layer"]["one_stream_ms_per_step"] = round(r["serial_ms"], 5)
     return line
@@ -288,6 +341,8 @@ def main():
                     help="also time every node's share of the expert FFN for N expert nodes, plain deployment "
                          "against the greedy plan with S slots per node (hot experts get copies)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="time the streaming-read and register-only MFMA probes even with --no-cpu-baseline")
     ap.add_argument("--cpu-sample-tokens", type=int, default=256)
     ap.add_argument("--calibrate", action="store_true",
                     help="only run a plain device copy of known size (1 GiB) a few times and print its rate; "
@@ -351,7 +406,7 @@ def main():
             print("[bench] timing the CPU oracle on a sample ...", file=sys.stderr, flush=True)
             from oracle import moe_oracle  # the cpu_baseline leg is the only user of the oracle here
             cpu = cpu_baseline(c, args.seed, W, x, logits, moe_oracle, args.cpu_sample_tokens)
-        return result_line(c, args.steps, args.warmup, r, R, cpu)
+        return result_line(c, args.steps, args.warmup, r, R, cpu, measure_ceilings(paths[0], B, torch) if want_cpu or args.ceilings else None)
 
     lines = []
     if args.sweep and cfg.name.startswith("mixtral"):

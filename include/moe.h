@@ -213,6 +213,24 @@ moe_status moe_expert_ffn_segments(moe_ctx* ctx, int32_t T, int32_t n_segs, int3
 moe_status moe_combine(moe_ctx* ctx, int32_t T, const void* y, const int32_t* pos, const float* topk_w,
                        void* out, void* stream);
 
+/*
+ * Probes for the roofline's two denominators (Section 2.3: a GEMM is memory-bound below the ridge batch
+ * F / B and compute-bound above it; B = memory bandwidth, F = peak compute). They compute no part of
+ * the layer: a benchmark times them next to the layer's kernels to state what this chip reaches.
+ *   moe_probe_stream_read: every wavefront reads its own contiguous share of buf[bytes] (device) with
+ *     the non-temporal 16-byte loads of the weight stream; *bytes_read (host, may be NULL) receives
+ *     the bytes actually read (bytes rounded down to whole loads per wavefront).
+ *   moe_probe_mfma: `workgroups` x 4 wavefronts each issue iters x 16 v_mfma_f32_32x32x16_bf16 from
+ *     registers; the operands are the first 2 KiB of `operands` (device; pass real weights: the
+ *     matrix cores' clock under load depends on the bit patterns multiplied); *flops (host, may be
+ *     NULL) receives the floating-point operations of the launch.
+ * `sink` is 16 bytes of device memory the kernels may write. Both return after enqueueing.
+ */
+moe_status moe_probe_stream_read(moe_ctx* ctx, const void* buf, size_t bytes, void* sink, size_t* bytes_read,
+                                 void* stream);
+moe_status moe_probe_mfma(moe_ctx* ctx, const void* operands, int32_t iters, int32_t workgroups, void* sink,
+                          double* flops, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,8 @@ _DTYPES = {"f32": (MOE_F32, torch.float32), "bf16": (MOE_BF16, torch.bfloat16)}
 
 EXPORTS = ("moe_create", "moe_destroy", "moe_last_error", "moe_status_string", "moe_packed_weight_bytes",
            "moe_pack_weights", "moe_route", "moe_gate_route", "moe_dispatch", "moe_expert_ffn", "moe_ffn_input", "moe_ffn_output",
-           "moe_combine", "moe_plan_experts", "moe_slot_segments", "moe_expert_ffn_segments", "moe_route_dispatch")
+           "moe_combine", "moe_plan_experts", "moe_slot_segments", "moe_expert_ffn_segments", "moe_route_dispatch",
+           "moe_probe_stream_read", "moe_probe_mfma")
 
 
 class MoeConfig(ctypes.Structure):
@@ -73,6 +74,9 @@ def load_library() -> ctypes.CDLL:
     lib.moe_plan_experts.argtypes = [i32, i32, i32, dp, ctypes.c_double, ip, ip, ip, dp]
     lib.moe_slot_segments.argtypes = [vp, i32] + [vp] * 6 + [vp]
     lib.moe_expert_ffn_segments.argtypes = [vp, i32, i32, i32] + [vp] * 7 + [vp]
+    lib.moe_probe_stream_read.argtypes = [vp, vp, ctypes.c_size_t, vp, ctypes.POINTER(ctypes.c_size_t), vp]
+    lib.moe_probe_mfma.argtypes = [vp, vp, i32, i32, vp, dp, vp]
+    lib.moe_probe_stream_read.restype = lib.moe_probe_mfma.restype = ctypes.c_int
     for name in ("moe_pack_weights", "moe_route", "moe_gate_route", "moe_dispatch", "moe_expert_ffn", "moe_ffn_input", "moe_ffn_output",
            "moe_combine", "moe_plan_experts", "moe_slot_segments", "moe_expert_ffn_segments", "moe_route_dispatch"):
         getattr(lib, name).restype = ctypes.c_int
@@ -194,6 +198,22 @@ def moe_expert_ffn_segments(ctx, T, n_segs, rows_hint, xp, seg_begin, seg_end, s
     _check(ctx, load_library().moe_expert_ffn_segments(ctx, T, n_segs, rows_hint, _ptr(xp), _ptr(seg_begin),
                                                        _ptr(seg_end), _ptr(seg_expert), _ptr(packed_w), _ptr(h_ws),
                                                        _ptr(y), _stream(stream)))
+
+
+def moe_probe_stream_read(ctx, buf, nbytes, sink, stream=None) -> int:
+    """Enqueue the streaming-read probe over buf[:nbytes]; returns the bytes it reads."""
+    got = ctypes.c_size_t(0)
+    _check(ctx, load_library().moe_probe_stream_read(ctx, _ptr(buf), nbytes, _ptr(sink), ctypes.byref(got),
+                                                     _stream(stream)))
+    return got.value
+
+
+def moe_probe_mfma(ctx, operands, iters, workgroups, sink, stream=None) -> float:
+    """Enqueue the register-only MFMA probe; returns the flops of the launch."""
+    flops = ctypes.c_double(0.0)
+    _check(ctx, load_library().moe_probe_mfma(ctx, _ptr(operands), iters, workgroups, _ptr(sink), ctypes.byref(flops),
+                                              _stream(stream)))
+    return flops.value
 
 
 class NodeShare:

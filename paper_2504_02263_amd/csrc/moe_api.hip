@@ -211,6 +211,28 @@ moe_status moe_expert_ffn_segments(moe_ctx* ctx, int32_t T, int32_t n_segs, int3
   return finish(ctx, "moe_expert_ffn_segments", err);
 }
 
+moe_status moe_probe_stream_read(moe_ctx* ctx, const void* buf, size_t bytes, void* sink, size_t* bytes_read,
+                                 void* stream) {
+  const void* ptrs[] = {buf, sink};
+  const moe_status s = check_call(ctx, "moe_probe_stream_read", 0, ptrs, 2);
+  if (s != MOE_OK) return s;
+  if (bytes_read) *bytes_read = moe::probe_stream_read_bytes(bytes);
+  return finish(ctx, "moe_probe_stream_read",
+                moe::launch_probe_stream_read(buf, bytes, sink, static_cast<hipStream_t>(stream)));
+}
+
+moe_status moe_probe_mfma(moe_ctx* ctx, const void* operands, int32_t iters, int32_t workgroups, void* sink,
+                          double* flops, void* stream) {
+  const void* ptrs[] = {operands, sink};
+  const moe_status s = check_call(ctx, "moe_probe_mfma", 0, ptrs, 2);
+  if (s != MOE_OK) return s;
+  if (iters < 0 || iters > (1 << 24) || workgroups < 0 || workgroups > (1 << 20))
+    return fail(ctx, MOE_ERR_INVALID_ARG, "moe_probe_mfma: iters = %d or workgroups = %d out of range", iters, workgroups);
+  if (flops) *flops = (double)workgroups * 4.0 * iters * 16.0 * (2.0 * 32 * 32 * 16);
+  return finish(ctx, "moe_probe_mfma",
+                moe::launch_probe_mfma(operands, iters, workgroups, sink, static_cast<hipStream_t>(stream)));
+}
+
 moe_status moe_combine(moe_ctx* ctx, int32_t T, const void* y, const int32_t* pos, const float* topk_w, void* out,
                        void* stream) {
   const void* ptrs[] = {y, pos, topk_w, out};

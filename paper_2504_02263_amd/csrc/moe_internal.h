@@ -43,5 +43,10 @@ hipError_t launch_slot_segments(const int32_t* slot_expert, const int32_t* slot_
                                 const int32_t* offsets, int n_slots, int E, int32_t* seg_begin, int32_t* seg_end,
                                 hipStream_t stream);
 size_t packed_weight_bytes(const moe_config& cfg);
+// Roofline probes: a streaming read of `bytes` (rounded down to whole loads: probe_stream_read_bytes) and
+// `iters` x 16 MFMAs per wavefront from registers on `workgroups` x 4 wavefronts.
+hipError_t launch_probe_stream_read(const void* buf, size_t bytes, void* sink, hipStream_t stream);
+size_t probe_stream_read_bytes(size_t bytes);
+hipError_t launch_probe_mfma(const void* operands, int iters, int workgroups, void* sink, hipStream_t stream);
 
 }  // namespace moe

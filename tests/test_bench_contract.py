@@ -42,5 +42,8 @@ def test_json_line_fields_on_the_small_layer():
     assert abs(j["value"] - j["config"]["T"] / (j["ms_per_step"] * 1e-3)) <= 1e-3 * j["value"]
     rf = j["roofline"]
     assert rf["bound"] in ("hbm", "mfma", "alu") and abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-3
+    assert j["ceilings"]["stream_read_GB/s"] > 0 and j["ceilings"]["stream_read_bytes"] > 0
+    assert len(rf["launch_ms_p10_p50_p90"]) == 3 and set(j["layer"]["calls_rates"]) == set(j["layer"]["calls_ms"])
+    assert sum(j["config"]["tokens_per_expert"]) == j["config"]["T"] * j["config"]["k"]
     cpu = j["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0

@@ -362,3 +362,20 @@ def test_route_dispatch_one_call_equals_the_two_calls(T, E, k, d, dtype):
         assert torch.equal(getattr(a, name), getattr(b, name)), name
     a.close()
     b.close()
+
+
+def test_roofline_probes_run_and_report_their_work():
+    """The two measuring kernels: argument handling and reported work (their rates are bench.py's business)."""
+    path = B.MoEPath(8, 128, 128, 2, 1, "bf16")
+    buf = torch.randint(0, 255, (8 * 1024 * 1024 + 100,), dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(16, dtype=torch.float32, device="cuda")
+    got = B.moe_probe_stream_read(path.ctx, buf, buf.numel(), sink)
+    assert 0 < got <= buf.numel() and got % (4096 * 1024) == 0       # whole 1 KiB loads for each of 4096 wavefronts
+    assert B.moe_probe_stream_read(path.ctx, buf, 1000, sink) == 0     # too small for one load per wavefront: nothing runs
+    flops = B.moe_probe_mfma(path.ctx, buf, 10, 8, sink)
+    assert flops == 8 * 4 * 10 * 16 * 2 * 32 * 32 * 16
+    torch.cuda.synchronize()
+    assert float(sink.abs().sum()) == 0.0                              # the sink is only a place the kernels may write
+    with pytest.raises(B.MoeError):
+        B.moe_probe_mfma(path.ctx, buf, -1, 8, sink)
+    path.close()
