@@ -50,6 +50,7 @@ struct TileLoc {
   int rows;     // rows of the m-tile (<= BM)
   int within;   // position inside the expert's block of `per_tile`-sized groups (see locate_tile)
   int tiles;    // m-tiles of this expert
+  int step;     // rows of the expert's full-height tiles (its last tile may hold fewer)
 };
 
 // Work items are ordered segment-major ("expert" below = segment): expert e owns tiles_e * per_tile consecutive positions,
@@ -61,7 +62,7 @@ struct TileLoc {
 template <bool BALANCED>
 __device__ __forceinline__ TileLoc locate_tile(const Segs& segs, int BM, int per_tile, int pos) {
   __shared__ int s_wave_total[8];
-  __shared__ int s_loc[5];
+  __shared__ int s_loc[6];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   int lo = 0, hi = 0;
   if (tid < segs.count) {
@@ -90,6 +91,7 @@ __device__ __forceinline__ TileLoc locate_tile(const Segs& segs, int BM, int per
     s_loc[2] = max(0, min(step, hi - r0));
     s_loc[3] = q / nt;
     s_loc[4] = nt;
+    s_loc[5] = step;
   }
   __syncthreads();
   TileLoc t;
@@ -98,6 +100,7 @@ __device__ __forceinline__ TileLoc locate_tile(const Segs& segs, int BM, int per
   t.rows = s_loc[2];
   t.within = s_loc[3];
   t.tiles = s_loc[4];
+  t.step = s_loc[5];
   return t;
 }
 
@@ -511,7 +514,11 @@ __global__ __launch_bounds__(256) void ffn_bf16_wide_kernel(const u32x4* __restr
   const bool has_n = pair < NP;
   const int rows = loc.rows;
   const u32x4* wbase = Wp + ((size_t)wexp * NP + (has_n ? pair : 0)) * (K / 16) * 128 + (threadIdx.x & 63);
-  const int mu = __builtin_amdgcn_readfirstlane((rows + 31) / 32);  // live 32-row groups, 1..8
+  // 32-row groups the tile runs, 1..8. The m-tiles of an expert share their weights through L2 only
+  // while they sweep K side by side, so they must take the same time: an expert's shorter last tile
+  // runs the schedule of its full-height tiles (its missing rows are clamped loads and skipped
+  // stores; at most one row group in a tile of seven or eight is wasted).
+  const int mu = __builtin_amdgcn_readfirstlane(loc.tiles > 1 ? loc.step / 32 : (rows + 31) / 32);
   // Tiles of up to 5 row groups have registers to spare for a deeper weight ring (K / 64 must divide
   // by it). An expert with a single m-tile reads its weights once: non-temporal loads, as in the
   // streaming kernel; otherwise cached loads, since the expert's m-tiles share the weights in L2.
