@@ -6,7 +6,7 @@ A step is one pass of the whole path (moe_route_dispatch [= moe_route, moe_dispa
 default workload is the Mixtral-8x22B-shaped decode micro-batch (d=6144, f=16384, E=8, top-2,
 bf16, T=256), the configuration the headline metric is quoted on.
 
-Prints ONE JSON line (see README/DESIGN for the fields). `roofline` is for the dominant kernel
+Prints ONE JSON line. `roofline` is for the dominant kernel
 (the fused gate|up "FFN Input" GEMM): algorithmic bytes or flops per launch over its average
 duration, measured with events on the launch stream inside the timed region. `cpu_baseline` is
 the CPU oracle, as it stands, timed on this machine's host cores on a bounded sample.
