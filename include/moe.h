@@ -13,7 +13,8 @@
  *   - Notation: T tokens, d hidden size (paper: h), f expert intermediate size (paper: h'),
  *     E experts, k experts per token (paper: K), A = T*k assignments.
  *   - Every tensor pointer is a DEVICE pointer owned by the caller, row-major and contiguous,
- *     16-byte aligned. The library allocates no device memory and keeps no device state: each
+ *     16-byte aligned (the exceptions say so: moe_plan_experts is a host function, and the two
+ *     probes return a scalar through a host pointer). The library allocates no device memory and keeps no device state: each
  *     call is a pure function of its arguments, so calls on different streams never share
  *     anything but their arguments.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream). All work is enqueued
