@@ -233,6 +233,39 @@ def measure_ceilings(path, B, torch, reps=5):
     return out
 
 
+def vendor_gemm_yardstick(cfg, torch, reps=10):
+    """The vendor GEMM library (torch.matmul into preallocated outputs) on the same job as the two expert
+    GEMMs: one call per expert, distinct random weights, uniform rows per expert, nothing fused. A yardstick
+    printed beside the result, not part of the path."""
+    E, d, f = cfg.E, cfg.d, cfg.f
+    M = max(1, cfg.T * cfg.k // E // cfg.micro_batches)
+    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    out = {"vendor_gemm": f"{E} calls per stage, {M} rows each", "note": "torch.matmul, random data, no activation fused"}
+    for name, N, K in (("ffn_input", 2 * f, d), ("ffn_output", d, f)):
+        a = [torch.randn(M, K, device="cuda").to(dt) for _ in range(E)]
+        b = [(torch.randn(N, K, device="cuda") * K ** -0.5).to(dt) for _ in range(E)]
+        c = [torch.empty(M, N, device="cuda", dtype=dt) for _ in range(E)]
+
+        def step():
+            for e in range(E):
+                torch.matmul(a[e], b[e].t(), out=c[e])
+        for _ in range(3):
+            step()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            step()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        out[name] = {"ms": round(ms, 4), "TFLOP/s": round(2.0 * E * M * N * K / (ms * 1e-3) / 1e12, 1),
+                     "weight_GB/s": round(E * N * K * (2 if cfg.dtype == "bf16" else 4) / (ms * 1e-3) / 1e9, 1)}
+        del a, b, c
+        torch.cuda.empty_cache()
+    return out
+
+
 def roofline_entry(cfg, cost, ffn_in_ms, R):
     t = ffn_in_ms * 1e-3
     if cfg.dtype == "bf16":
@@ -341,6 +374,9 @@ def main():
                     help="also time every node's share of the expert FFN for N expert nodes, plain deployment "
                          "against the greedy plan with S slots per node (hot experts get copies)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="also time the vendor GEMM library on the two expert GEMMs of this workload (one call per "
+                         "expert, distinct weights, uniform rows) and print it as an extra JSON line")
     ap.add_argument("--ceilings", action="store_true",
                     help="time the streaming-read and register-only MFMA probes even with --no-cpu-baseline")
     ap.add_argument("--cpu-sample-tokens", type=int, default=256)
@@ -422,6 +458,10 @@ def main():
         fit = R.fit_expert_time([p[0] for p in pts], [p[1] for p in pts], split=128)
         fit["roofline_ridge_b"] = R.ridge_batch(R.MI355X_BF16_DENSE_FLOPS, R.MI355X_HBM_BYTES_PER_S)
         print(json.dumps({"expert_time_model": "T_e[ms] = k3*b_e + k4", "points": pts, "fit": fit}), flush=True)
+    if args.vendor_gemm:
+        y = vendor_gemm_yardstick(cfg, torch)
+        y["this_library_ms"] = {n: lines[-1]["layer"]["calls_ms"][n] for n in ("ffn_input", "ffn_output")}
+        print(json.dumps(y), flush=True)
     if args.expert_plan:
         N, S = (int(v) for v in args.expert_plan.split(","))
         if cfg.E % N or N * S < cfg.E:
