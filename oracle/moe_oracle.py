@@ -119,7 +119,15 @@ def silu(z: np.ndarray) -> np.ndarray:
     return z / (1.0 + np.exp(-z))
 
 
-def expert_ffn(xp: np.ndarray, offsets: np.ndarray, expert_weights, return_h: bool = False):
+def round_to_bf16(a: np.ndarray) -> np.ndarray:
+    """float64 values rounded to the nearest bfloat16 (ties to even) via float32, returned as float64.
+    Diagnostic only (see expert_ffn's `store_bf16`): it mimics where a bf16 implementation stores."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    r = (u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))) & np.uint32(0xFFFF0000)
+    return r.view(np.float32).astype(np.float64)
+
+
+def expert_ffn(xp: np.ndarray, offsets: np.ndarray, expert_weights, return_h: bool = False, store_bf16: bool = False):
     """Per-expert SwiGLU FFN over the expert-contiguous rows (Section 4.2, Table 3: "FFN Input"
     (b_e, h) x (h, h') and "FFN Output" (b_e, h') x (h', h), with tensor-parallel degree 1).
 
@@ -128,6 +136,9 @@ def expert_ffn(xp: np.ndarray, offsets: np.ndarray, expert_weights, return_h: bo
 
       h[r, :] = silu(xp[r, :] W_gate_e^T) * (xp[r, :] W_up_e^T)
       y[r, :] = h[r, :] W_down_e^T              for r in expert e's segment
+
+    store_bf16=True is a diagnostic, not the definition: h and y are rounded to bfloat16 where a bf16
+    implementation stores them, so that what is left of a comparison is accumulation order alone.
 
     Returns y[A, d] float64 (and h[A, f] float64 if return_h).
     """
@@ -145,7 +156,9 @@ def expert_ffn(xp: np.ndarray, offsets: np.ndarray, expert_weights, return_h: bo
         g = rows @ widen(w_gate).T
         u = rows @ widen(w_up).T
         h = silu(g) * u
-        y[lo:hi] = h @ widen(w_down).T
+        if store_bf16:
+            h = round_to_bf16(h)
+        y[lo:hi] = round_to_bf16(h @ widen(w_down).T) if store_bf16 else h @ widen(w_down).T
         if return_h:
             if h_all is None:
                 h_all = np.zeros((A, h.shape[1]), dtype=np.float64)

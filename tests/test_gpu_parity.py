@@ -379,3 +379,24 @@ def test_roofline_probes_run_and_report_their_work():
     with pytest.raises(B.MoeError):
         B.moe_probe_mfma(path.ctx, buf, -1, 8, sink)
     path.close()
+
+
+@pytest.mark.parametrize("T,d,f,E,k", [(160, 256, 512, 8, 2), (1100, 256, 384, 3, 2), (333, 128, 384, 64, 6)])
+def test_ffn_against_the_bf16_store_diagnostic(T, d, f, E, k):
+    """A sharper look at the GEMMs than the 1e-2 bound allows: against the oracle that rounds h and y to bf16
+    where the GPU stores them, what is left is float32 accumulation order and the few roundings it flips
+    (a flip is one bf16 ulp, 2^-8 relative, on roughly one value in a thousand): a few 1e-4 at most."""
+    cfg = small_cfg(T, d, f, E, k, "bf16")
+    x = synth.make_activations(cfg, 6)
+    logits = synth.make_logits(cfg, 6)
+    W = synth.make_all_expert_weights(cfg, 6, workers=4)
+    get = lambda e: (W[0][e], W[1][e], W[2][e])
+    idx, w, counts, offsets = O.route(logits, k)
+    xp, pos, src = O.dispatch(x, idx, offsets)
+    y_ref, h_ref = O.expert_ffn(xp, offsets, get, return_h=True, store_bf16=True)
+    path = run_layer(cfg, x, logits, W)
+    A = T * k
+    eh, ey = rel_fro(host(path.h)[:A], h_ref), rel_fro(host(path.y)[:A], y_ref)
+    print(f"{cfg.name}: against the bf16-store diagnostic: h {eh:.2e}  y {ey:.2e}")
+    assert eh <= 3e-4 and ey <= 3e-4
+    path.close()

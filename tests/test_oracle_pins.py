@@ -385,3 +385,22 @@ def test_tiny_config_end_to_end_invariants():
     assert res["out"].shape == (cfg.T, cfg.d) and np.isfinite(res["out"]).all()
     # x ~ N(0,1), weights N(0,1/fan_in): outputs are O(1), not degenerate
     assert 0.01 < np.abs(res["out"]).mean() < 10
+
+
+def test_bf16_store_diagnostic_rounds_like_the_input_generator_and_stays_close():
+    """round_to_bf16 against the generators' own float32 -> bfloat16 conversion (written separately), and the
+    store_bf16 diagnostic against the definition: it may move y by bf16 rounding only."""
+    rng = _rng(77)
+    a = rng.standard_normal(5000) * np.exp(rng.uniform(-20, 20, 5000))
+    a[:4] = [0.0, -0.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8]           # two exact ties: to even
+    via_bits = O.widen(synth.f32_to_bf16_bits(a.astype(np.float32)))
+    np.testing.assert_array_equal(O.round_to_bf16(a), via_bits)
+    assert O.round_to_bf16(np.array([1.0 + 2.0 ** -8]))[0] == 1.0 and O.round_to_bf16(np.array([1.0 + 3 * 2.0 ** -8]))[0] == 1.0 + 2.0 ** -6
+    E, d, f = 3, 16, 24
+    offsets = np.array([0, 5, 5, 12])
+    xp = rng.standard_normal((12, d))
+    W = [(rng.standard_normal((f, d)) / 4, rng.standard_normal((f, d)) / 4, rng.standard_normal((d, f)) / 5) for _ in range(E)]
+    y = O.expert_ffn(xp, offsets, W)
+    yb = O.expert_ffn(xp, offsets, W, store_bf16=True)
+    err = np.linalg.norm(yb - y) / np.linalg.norm(y)
+    assert 1e-4 < err < 2 ** -7                                          # two bf16 roundings, nothing more
