@@ -400,3 +400,20 @@ def test_ffn_against_the_bf16_store_diagnostic(T, d, f, E, k):
     print(f"{cfg.name}: against the bf16-store diagnostic: h {eh:.2e}  y {ey:.2e}")
     assert eh <= 3e-4 and ey <= 3e-4
     path.close()
+
+
+@pytest.mark.parametrize("T,d,f,E,k,dtype", [(1, 128, 128, 1, 1, "bf16"), (1, 128, 128, 2, 2, "f32"), (2, 128, 256, 256, 64, "bf16"),
+                                             (700, 128, 128, 1, 1, "bf16"), (257, 128, 128, 2, 2, "bf16")])
+def test_smallest_shapes_and_single_tokens(T, d, f, E, k, dtype):
+    """The smallest legal hidden sizes (two K chunks), one expert, one token, and 256 experts with 64 picks."""
+    cfg = small_cfg(T, d, f, E, k, dtype)
+    x = synth.make_activations(cfg, 8)
+    logits = synth.make_logits(cfg, 8)
+    W = synth.make_all_expert_weights(cfg, 8, workers=4)
+    ref = O.moe_layer(x, logits, k, lambda e: (W[0][e], W[1][e], W[2][e]))
+    path = run_layer(cfg, x, logits, W)
+    check_integers(path, ref, T, k)
+    err = rel_fro(host(path.out)[:T], ref["out"])
+    print(f"{cfg.name}: rel-Frobenius out {err:.2e}")
+    assert err <= TOL[dtype]
+    path.close()
