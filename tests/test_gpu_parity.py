@@ -417,3 +417,35 @@ def test_smallest_shapes_and_single_tokens(T, d, f, E, k, dtype):
     print(f"{cfg.name}: rel-Frobenius out {err:.2e}")
     assert err <= TOL[dtype]
     path.close()
+
+
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        E = int(rng.choice([1, 2, 3, 5, 8, 12, 16, 24, 40, 64, 100]))
+        k = int(rng.integers(1, min(E, 8) + 1))
+        d = 128 * int(rng.integers(1, 4))
+        f = 128 * int(rng.integers(1, 5))
+        T = int(rng.choice([1, 7, 33, 64, 129, 300, 640, 1500]))
+        skew = float(rng.choice([0.0, 1.0, 3.0]))
+        cases.append((T, d, f, E, k, "bf16" if rng.random() < 0.8 else "f32", skew))
+    return cases
+
+
+@pytest.mark.parametrize("T,d,f,E,k,dtype,skew", _random_cases(24, 2024))
+def test_seeded_random_layers(T, d, f, E, k, dtype, skew):
+    """A seeded sweep over shapes nobody picked by hand: odd expert counts, every k, skewed loads (so tiles of
+    every height and both GEMM kernels occur), each checked like the hand-picked cases."""
+    cfg = small_cfg(T, d, f, E, k, dtype)
+    x = synth.make_activations(cfg, 31)
+    logits = synth.make_logits(cfg, 31)
+    if skew:
+        logits = (logits - skew * np.log(np.arange(1, E + 1, dtype=np.float32))).astype(np.float32)
+    W = synth.make_all_expert_weights(cfg, 31, workers=4)
+    ref = O.moe_layer(x, logits, k, lambda e: (W[0][e], W[1][e], W[2][e]))
+    path = run_layer(cfg, x, logits, W)
+    check_integers(path, ref, T, k)
+    err = rel_fro(host(path.out)[:T], ref["out"])
+    assert err <= TOL[dtype], (cfg.name, err)
+    path.close()
