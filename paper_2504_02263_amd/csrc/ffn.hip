@@ -42,6 +42,7 @@ struct Segs {
   int count;              // segments, <= 256
   int experts;            // experts in the packed weights
   int rows_cap;           // rows the activation buffers hold; ranges are clipped to it
+  int tall_first;         // large-batch kernel: order the segments by tile height (see locate_tile)
 };
 
 struct TileLoc {
@@ -53,14 +54,21 @@ struct TileLoc {
   int step;     // rows of the expert's full-height tiles (its last tile may hold fewer)
 };
 
-// Work items are ordered segment-major ("expert" below = segment): expert e owns tiles_e * per_tile consecutive positions,
-// tiles_e = ceil(c_e / BM). Position q inside an expert's block maps to m-tile q % tiles_e and
-// `within` = q / tiles_e, so the m-tiles that share one group of weight columns are neighbours.
+// Work items are ordered segment-major ("expert" below = segment). Expert e owns
+// tiles_e * per_tile consecutive positions, tiles_e = ceil(c_e / BM). Position q inside an expert's
+// block maps to m-tile q % tiles_e and `within` = q / tiles_e, so the m-tiles that share one group
+// of weight columns are neighbours.
+// Order of the segments: by index, or (TALL_FIRST and segs.tall_first) segments with taller tiles
+// first, equal heights by index. A launch of only a few rounds of workgroups then ends with its
+// shortest tiles instead of a late, lonely tall one (an expert that needs a second tile; skewed
+// loads). Long launches keep index order: there the mix of tall (matrix-core-heavy) and short
+// (memory-heavy) tiles running side by side is worth more than the shorter tail.
 // BALANCED: the expert's rows are split evenly over its tiles in multiples of 32 rows (so
 // 1072 rows with BM = 256 become 224 + 224 + 224 + 224 + 176, not 4 x 256 + 48).
 // All threads of the workgroup (>= 256, one per expert) must call this.
-template <bool BALANCED>
+template <bool BALANCED, bool TALL_FIRST = false>
 __device__ __forceinline__ TileLoc locate_tile(const Segs& segs, int BM, int per_tile, int pos) {
+  __shared__ int2 s_key[TALL_FIRST ? 256 : 1];  // (tile height, tiles) of every segment
   __shared__ int s_wave_total[8];
   __shared__ int s_loc[6];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -69,22 +77,44 @@ __device__ __forceinline__ TileLoc locate_tile(const Segs& segs, int BM, int per
     lo = max(0, min(segs.begin[tid], segs.rows_cap));
     hi = max(lo, min(segs.end[tid], segs.rows_cap));
   }
-  const int nt = (hi - lo + BM - 1) / BM;
-  int incl = nt;
+  const int rows = hi - lo;
+  const int nt = (rows + BM - 1) / BM;
+  const int step = nt == 0 ? 0 : BALANCED ? (((rows + nt - 1) / nt + 31) & ~31) : BM;  // rows per tile
+  const bool by_height = TALL_FIRST && segs.tall_first;  // uniform over the grid
+  int excl;  // tiles of the segments ordered before this one
+  if (by_height) {
+    if (tid < 256) s_key[tid] = make_int2(step, nt);
+    if (tid == 0) s_loc[0] = -1;
+    __syncthreads();
+    excl = 0;
+    if (tid < segs.count && nt > 0) {
+      for (int o0 = 0; o0 < segs.count; o0 += 8) {
+        int2 key[8];  // eight broadcast reads in flight, then branch-free arithmetic (entries past count hold 0 tiles)
 #pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const int o = __shfl_up(incl, off);
-    if (lane >= off) incl += o;
+        for (int j = 0; j < 8; ++j) key[j] = s_key[min(o0 + j, 255)];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int before = (key[j].x > step) | ((key[j].x == step) & (o0 + j < tid));
+          excl += key[j].y & -before;
+        }
+      }
+    }
+  } else {
+    int incl = nt;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int o = __shfl_up(incl, off);
+      if (lane >= off) incl += o;
+    }
+    if (lane == 63 && w < 8) s_wave_total[w] = incl;
+    if (tid == 0) s_loc[0] = -1;
+    __syncthreads();
+    excl = incl - nt;
+    for (int ww = 0; ww < w && ww < 4; ++ww) excl += s_wave_total[ww];  // experts live in the first 4 wavefronts
   }
-  if (lane == 63 && w < 8) s_wave_total[w] = incl;
-  if (tid == 0) s_loc[0] = -1;
-  __syncthreads();
-  int excl = incl - nt;
-  for (int ww = 0; ww < w && ww < 4; ++ww) excl += s_wave_total[ww];  // experts live in the first 4 wavefronts
   const int first = excl * per_tile;
-  if (nt > 0 && pos >= first && pos < first + nt * per_tile) {
+  if (tid < segs.count && nt > 0 && pos >= first && pos < first + nt * per_tile) {
     const int q = pos - first;
-    const int step = BALANCED ? (((hi - lo + nt - 1) / nt + 31) & ~31) : BM;  // rows per tile
     const int r0 = lo + (q % nt) * step;
     s_loc[0] = tid;
     s_loc[1] = r0;
@@ -505,7 +535,7 @@ __global__ __launch_bounds__(256) void ffn_bf16_wide_kernel(const u32x4* __restr
   const int groups = (NP + 3) / 4;
   const int groups_per_xcd = (groups + 7) / 8;
   const int xcd = blockIdx.x & 7;
-  const TileLoc loc = locate_tile<true>(segs, kWideBM, groups_per_xcd, blockIdx.x >> 3);
+  const TileLoc loc = locate_tile<true, true>(segs, kWideBM, groups_per_xcd, blockIdx.x >> 3);
   if (loc.expert < 0) return;
   const int group = loc.within * 8 + ((xcd + loc.expert) & 7);  // rotate per expert: evens out a group count that is not a multiple of 8
   const int wexp = segment_expert(segs, loc.expert);
@@ -625,10 +655,19 @@ void launch_bf16(const void* X, const Segs& segs, const void* Wp, void* C, int A
 }
 
 template <bool GATEUP>
-void launch_bf16_wide(const void* X, const Segs& segs, const void* Wp, void* C, int A, int N, int K,
+void launch_bf16_wide(const void* X, Segs segs, const void* Wp, void* C, int A, int rows_hint, int N, int K,
                       hipStream_t stream) {
   const int NP = GATEUP ? N / 32 : N / 64;
   const int groups_per_xcd = ((NP + 3) / 4 + 7) / 8;
+  // Expected workgroups with a tile: about rows / 256 + half a tile per segment, times the column
+  // groups. Up to four rounds of 256 compute units the tail decides the time: tall tiles first.
+  const float est = ((float)rows_hint / kWideBM + 0.5f * segs.count) * ((NP + 3) / 4);
+  // Tuning knob (read once): MOE_FFN_TALL_FIRST=0 / 1 forces index order / tall tiles first.
+  static const int forced = [] {
+    const char* v = getenv("MOE_FFN_TALL_FIRST");
+    return v ? atoi(v) : -1;
+  }();
+  segs.tall_first = forced >= 0 ? forced : est <= 4.f * 256.f;
   const dim3 grid(8 * groups_per_xcd * max_m_tiles(A, segs.count, kWideBM)), block(256);
   hipLaunchKernelGGL((ffn_bf16_wide_kernel<GATEUP>), grid, block, 0, stream, static_cast<const u32x4*>(X), segs,
                      static_cast<const u32x4*>(Wp), static_cast<__bf16*>(C), N, K);
@@ -694,7 +733,7 @@ hipError_t launch_ffn_segments(const moe_config& cfg, int stage, const int32_t* 
                                const void* in, const void* packed, void* out, hipStream_t stream) {
   const int A = rows_bound;
   if (A == 0 || n_segs == 0) return hipSuccess;
-  const Segs segs{seg_begin, seg_end, seg_expert, n_segs, cfg.E, rows_cap};
+  Segs segs{seg_begin, seg_end, seg_expert, n_segs, cfg.E, rows_cap, 0};
   const size_t one = (size_t)cfg.E * cfg.d * cfg.f;  // elements of one matrix set
   const int N = stage == 0 ? cfg.f : cfg.d, K = stage == 0 ? cfg.d : cfg.f;
   if (cfg.dtype == MOE_BF16) {
@@ -718,12 +757,12 @@ hipError_t launch_ffn_segments(const moe_config& cfg, int stage, const int32_t* 
       if (want <= 32.f) launch_bf16<1, 2, 2, 8, 1, true, true>(in, segs, w, out, A, N, K, stream);
       else if (want <= 64.f) launch_bf16<2, 2, 2, 8, 1, true, true>(in, segs, w, out, A, N, K, stream);
       else if (stream128 || want <= wide_above) launch_bf16<4, 2, 2, 8, 1, true, true>(in, segs, w, out, A, N, K, stream);
-      else launch_bf16_wide<true>(in, segs, w, out, A, N, K, stream);
+      else launch_bf16_wide<true>(in, segs, w, out, A, rows_hint, N, K, stream);
     } else {
       if (want <= 32.f) launch_bf16<1, 1, 2, 8, 1, false, true>(in, segs, w, out, A, N, K, stream);
       else if (want <= 64.f) launch_bf16<2, 1, 2, 8, 1, false, true>(in, segs, w, out, A, N, K, stream);
       else if (stream128 || want <= wide_above) launch_bf16<4, 1, 2, 8, 1, false, true>(in, segs, w, out, A, N, K, stream);
-      else launch_bf16_wide<false>(in, segs, w, out, A, N, K, stream);
+      else launch_bf16_wide<false>(in, segs, w, out, A, rows_hint, N, K, stream);
     }
     return hipGetLastError();
   }
