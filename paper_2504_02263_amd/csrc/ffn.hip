@@ -78,8 +78,22 @@ __device__ __forceinline__ TileLoc locate_tile(const Segs& segs, int BM, int per
     hi = max(lo, min(segs.end[tid], segs.rows_cap));
   }
   const int rows = hi - lo;
-  const int nt = (rows + BM - 1) / BM;
-  const int step = nt == 0 ? 0 : BALANCED ? (((rows + nt - 1) / nt + 31) & ~31) : BM;  // rows per tile
+  int nt = (rows + BM - 1) / BM;
+  int step = nt == 0 ? 0 : BM;  // rows per tile
+  if (BALANCED && nt > 0) {
+    // All tiles of an expert run the schedule of its tallest tile, so the split is chosen by the row
+    // groups it schedules, tiles x ceil(groups / tiles): one tile more than necessary is taken when
+    // that schedules fewer groups and the tiles stay at least 6 groups tall (29 groups: 5 x 6 = 30
+    // instead of 4 x 8 = 32).
+    const int G = (rows + 31) >> 5;
+    int mu = (G + nt - 1) / nt;
+    const int mu1 = (G + nt) / (nt + 1);
+    if (mu1 >= 6 && (nt + 1) * mu1 < nt * mu) {
+      ++nt;
+      mu = mu1;
+    }
+    step = mu * 32;
+  }
   const bool by_height = TALL_FIRST && segs.tall_first;  // uniform over the grid
   int excl;  // tiles of the segments ordered before this one
   if (by_height) {
@@ -639,8 +653,9 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ 
   }
 }
 
-// Upper bound on the m-tiles of S segments holding at most A rows: sum ceil(c / BM) <= A / BM + min(S, A).
-inline int max_m_tiles(int A, int S, int BM) { return A / BM + (S < A ? S : A); }
+// Upper bound on the m-tiles of S segments holding at most A rows: sum ceil(c / BM) <= A / BM + min(S, A);
+// the balanced split of the large-batch kernel may take one more tile per segment.
+inline int max_m_tiles(int A, int S, int BM, int extra = 0) { return A / BM + (1 + extra) * (S < A ? S : A); }
 
 template <int MTW, int NW, int NST, int WN, int WM, bool GATEUP, bool NTL>
 void launch_bf16(const void* X, const Segs& segs, const void* Wp, void* C, int A, int N, int K, hipStream_t stream) {
@@ -668,7 +683,7 @@ void launch_bf16_wide(const void* X, Segs segs, const void* Wp, void* C, int A, 
     return v ? atoi(v) : -1;
   }();
   segs.tall_first = forced >= 0 ? forced : est <= 4.f * 256.f;
-  const dim3 grid(8 * groups_per_xcd * max_m_tiles(A, segs.count, kWideBM)), block(256);
+  const dim3 grid(8 * groups_per_xcd * max_m_tiles(A, segs.count, kWideBM, 1)), block(256);
   hipLaunchKernelGGL((ffn_bf16_wide_kernel<GATEUP>), grid, block, 0, stream, static_cast<const u32x4*>(X), segs,
                      static_cast<const u32x4*>(Wp), static_cast<__bf16*>(C), N, K);
 }
