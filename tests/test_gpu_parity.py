@@ -139,6 +139,8 @@ FFN_CASES = [
     (333, 128, 384, 64, 6, "bf16"), (64, 256, 512, 8, 2, "f32"), (300, 128, 384, 5, 3, "f32"),
     # large-batch kernel: shortest possible K loop (2 chunks), ragged multi-tile segments, one 32-row group
     (600, 128, 128, 2, 1, "bf16"), (1100, 256, 384, 3, 2, "bf16"), (150, 128, 256, 1, 1, "bf16"),
+    # large-batch kernel with many segments in a short launch (tiles ranked by height across 64 and 200 experts)
+    (2000, 128, 128, 64, 8, "bf16"), (3000, 128, 128, 200, 16, "bf16"),
 ]
 
 
