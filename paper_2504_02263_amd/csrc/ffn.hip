@@ -383,9 +383,9 @@ __global__ __launch_bounds__(64 * WN * WM) void ffn_bf16_kernel(const u32x4* __r
 //
 // Workgroup = 4 wavefronts, one per SIMD with the whole 512-entry register file: wavefront w owns
 // fragment pair `4 * group + w` and all rows of an m-tile of up to kWideBM = 256 rows (up to
-// 2 x 8 accumulator tiles = 256 registers). An expert's rows are split evenly over ceil(c_e / 256) tiles in
-// multiples of 32, so a tile has MU = 1..8 live 32-row groups and nothing is padded beyond the
-// last group. Same grid order and weight layout as above.
+// 2 x 8 accumulator tiles = 256 registers). An expert's rows are split evenly over its tiles in
+// multiples of 32 (see locate_tile), so a tile runs MU = 1..8 32-row groups. Same weight layout and
+// XCD mapping as above; the order of the experts in the queue is chosen per launch (locate_tile).
 //
 // With one wavefront per SIMD nothing hides LDS latency but the wavefront's own schedule, so the
 // k-step loop is software-pipelined by hand: token fragments are read R - 1 (row group, k-step)
@@ -561,7 +561,7 @@ __global__ __launch_bounds__(256) void ffn_bf16_wide_kernel(const u32x4* __restr
   // 32-row groups the tile runs, 1..8. The m-tiles of an expert share their weights through L2 only
   // while they sweep K side by side, so they must take the same time: an expert's shorter last tile
   // runs the schedule of its full-height tiles (its missing rows are clamped loads and skipped
-  // stores; at most one row group in a tile of seven or eight is wasted).
+  // stores; the split in locate_tile is chosen to keep that waste small).
   const int mu = __builtin_amdgcn_readfirstlane(loc.tiles > 1 ? loc.step / 32 : (rows + 31) / 32);
   // Tiles of up to 5 row groups have registers to spare for a deeper weight ring (K / 64 must divide
   // by it). An expert with a single m-tile reads its weights once: non-temporal loads, as in the
