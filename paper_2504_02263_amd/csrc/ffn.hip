@@ -515,26 +515,68 @@ __device__ __forceinline__ void wide_tile(const u32x4* __restrict__ X, const u32
   };
   for (int c0 = 0; c0 < NC; c0 += NST) static_for<0, NST>([&](auto st_) { stage(st_, c0 + decltype(st_)::value); });
 
-  if (!has_n) return;
+  // Epilogue. In the accumulators a lane holds 4 consecutive columns of one row per register quad, so
+  // storing them directly writes 16-byte pieces of 32 different rows per instruction, and the time a
+  // workgroup waits for those partial-line writes is pure overhead (up to a quarter of a short-K
+  // tile). The results are instead transposed through the slab (idle now: the K loop ended with a
+  // barrier) and leave as whole 16-byte units, consecutive lanes on consecutive units of a row.
+  // 8-byte slot (unit u, half fg) of row r sits at r * SL + ((u ^ g(r)) << 1 | fg); g(r) spreads the
+  // row-strided writes over the banks (2-way conflicts) and keeps the unit-strided reads conflict-free.
+  if constexpr (GATEUP) {
+    // Each wavefront owns 32 columns (64 bytes per row) but the four of a workgroup own 128
+    // consecutive ones: all write into one [32 MU rows][256 bytes] image, one barrier, and every
+    // store instruction then covers 4 full 256-byte row pieces.
+    const int w = tid >> 6;
+    uint2* ep8 = reinterpret_cast<uint2*>(slab);
+    if (has_n) {
 #pragma unroll
-  for (int m = 0; m < MU; ++m) {
-    const int row = m * 32 + frow;
-    if (row < rows) {
-      __bf16* crow = C + (size_t)(row0 + row) * N + 4 * fg;
-#pragma unroll
-      for (int i = 0; i < (GATEUP ? 1 : 2); ++i) {
-        const int tile = GATEUP ? pair : 2 * pair + i;
+      for (int m = 0; m < MU; ++m) {
+        const int r = m * 32 + frow;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           bf16x4 o;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            float v = acc[i][m][q * 4 + j];
-            if (GATEUP) v = silu(v) * acc[1][m][q * 4 + j];
-            o[j] = (__bf16)v;
-          }
-          *reinterpret_cast<bf16x4*>(crow + tile * 32 + 8 * q) = o;
+          for (int j = 0; j < 4; ++j) o[j] = (__bf16)(silu(acc[0][m][q * 4 + j]) * acc[1][m][q * 4 + j]);
+          ep8[r * 32 + ((((w * 4 + q) ^ (r & 15)) << 1) | fg)] = __builtin_bit_cast(uint2, o);
         }
+      }
+    }
+    __syncthreads();
+    const int ru = lane & 15;
+    const int col = (pair - w) * 32 + 8 * ru;      // columns of wavefronts past the last pair stay unwritten
+    __bf16* cbase = C + (size_t)row0 * N + col;
+#pragma unroll
+    for (int t = 0; t < 2 * MU; ++t) {
+      const int r = t * 16 + w * 4 + (lane >> 4);
+      const u32x4 v = slab[r * 16 + (ru ^ (r & 15))];
+      if (r < rows && col < N) *reinterpret_cast<u32x4*>(cbase + (size_t)r * N) = v;
+    }
+  } else {
+    // Each wavefront owns 64 columns, a full 128-byte line per row: it transposes one 32-row group
+    // at a time through a private 4 KiB piece of the slab. LDS operations of one wavefront execute
+    // in order, so no barrier is needed.
+    if (!has_n) return;
+    uint2* ep8 = reinterpret_cast<uint2*>(slab) + (tid >> 6) * 512;
+    const u32x4* ep16 = slab + (tid >> 6) * 256;
+    const int ru = lane & 7;
+    __bf16* cbase = C + (size_t)row0 * N + pair * 64 + 8 * ru;
+#pragma unroll
+    for (int m = 0; m < MU; ++m) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          bf16x4 o;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) o[j] = (__bf16)acc[i][m][q * 4 + j];
+          ep8[frow * 16 + ((((i * 4 + q) ^ ((frow >> 1) & 7)) << 1) | fg)] = __builtin_bit_cast(uint2, o);
+        }
+      }
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int r = t * 8 + (lane >> 3);         // row inside this 32-row group
+        const u32x4 v = ep16[r * 8 + (ru ^ ((r >> 1) & 7))];
+        if (m * 32 + r < rows) *reinterpret_cast<u32x4*>(cbase + (size_t)(m * 32 + r) * N) = v;
       }
     }
   }
