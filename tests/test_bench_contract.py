@@ -38,6 +38,7 @@ def test_json_line_fields_on_the_small_layer():
                 "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
         assert key in j, key
     assert j["n_gpus"] == 1 and j["steps"] == 3 and j["warmup"] == 1 and j["unit"] == "tokens/s"
+    assert j["warmup_steps_run"] >= j["warmup"]          # warm-up goes on until the clocks have settled
     assert j["config"]["workload"] == "tiny_fp32" and j["dtype"] == "f32" and j["data"] == "synthetic"
     assert abs(j["value"] - j["config"]["T"] / (j["ms_per_step"] * 1e-3)) <= 1e-3 * j["value"]
     rf = j["roofline"]

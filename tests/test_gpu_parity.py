@@ -235,6 +235,45 @@ def test_calls_run_on_the_given_stream():
     path.close()
 
 
+@pytest.mark.parametrize("T,d,f,E,k", [(200, 256, 512, 8, 2), (700, 256, 256, 16, 4)])
+def test_layer_replays_from_a_hip_graph(T, d, f, E, k):
+    """The hot calls allocate nothing, never synchronise and record no memset, so a caller may capture
+    the whole layer into a HIP graph. Every replay (new inputs in the same buffers, eager work and
+    synchronisations in between) must reproduce the eager result bit for bit."""
+    cfg = small_cfg(T, d, f, E, k, "bf16")
+    W = synth.make_all_expert_weights(cfg, 4, workers=4)
+    path = B.MoEPath(cfg.T, cfg.d, cfg.f, cfg.E, cfg.k, cfg.dtype)
+    path.pack_weights(dev(W[0]), dev(W[1]), dev(W[2]))
+    inputs = [(dev(synth.make_activations(cfg, s)), dev(synth.make_logits(cfg, s))) for s in (10, 11, 12, 13)]
+    eager = []
+    for xd, ld in inputs:
+        path.forward(xd, ld)
+        torch.cuda.synchronize()
+        eager.append([host(t).copy() for t in (path.topk_idx, path.offsets, path.pos, path.src, path.xp, path.y, path.out)])
+    xs, ls = torch.empty_like(inputs[0][0]), torch.empty_like(inputs[0][1])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up on the capture stream's side, as torch asks
+        xs.copy_(inputs[0][0]); ls.copy_(inputs[0][1])
+        path.forward(xs, ls)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        path.forward(xs, ls)
+    for rep in (1, 2, 3, 1, 0):
+        xs.copy_(inputs[rep][0]); ls.copy_(inputs[rep][1])
+        path.out.zero_(); path.y.zero_(); path.xp.zero_()          # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [host(t) for t in (path.topk_idx, path.offsets, path.pos, path.src, path.xp, path.y, path.out)]
+        for a, b in zip(got, eager[rep]):
+            assert (a == b).all(), f"replay of input {rep} differs from the eager run"
+    del graph
+    path.close()
+
+
 # ------------------------------------------------------------------------------- fused gate GEMM + routing
 
 @pytest.mark.parametrize("T,d,E,k,dtype", [(64, 256, 8, 2, "f32"), (257, 384, 16, 4, "bf16"), (1000, 512, 64, 6, "bf16"),
