@@ -451,8 +451,9 @@ __device__ __forceinline__ void wide_tile(const u32x4* __restrict__ X, const u32
 #pragma unroll
     for (int p = 0; p < MU; ++p) t0[p] = xrow[p][0];
 #pragma unroll
-    for (int p = 0; p < MU; ++p) t1[p] = xrow[p][min(1, NC - 1) * 8];
-    load_t(2);
+    for (int p = 0; p < MU; ++p) t1[p] = xrow[p][8];
+#pragma unroll
+    for (int p = 0; p < MU; ++p) treg[p] = xrow[p][16];  // K >= 256 (the launcher sees to it): chunks 1, 2 exist
     static_for<0, NST>([&](auto st_) {
 #pragma unroll
       for (int s = 0; s < 4; ++s) load_w_step(st_, decltype(st_)::value, s);
@@ -522,32 +523,37 @@ __device__ __forceinline__ void wide_tile(const u32x4* __restrict__ X, const u32
   // barrier) and leave as whole 16-byte units, consecutive lanes on consecutive units of a row.
   // 8-byte slot (unit u, half fg) of row r sits at r * SL + ((u ^ g(r)) << 1 | fg); g(r) spreads the
   // row-strided writes over the banks (2-way conflicts) and keeps the unit-strided reads conflict-free.
+  // The lane arithmetic below restarts from the thread id behind an opaque asm: otherwise the compiler
+  // computes the epilogue's addresses before the K loop and keeps them in registers across it, which
+  // the 7- and 8-group tiles cannot afford.
+  int etid = threadIdx.x;
+  asm volatile("" : "+v"(etid));
+  const int w = etid >> 6, elane = etid & 63, erow = elane & 31, eg = elane >> 5;
   if constexpr (GATEUP) {
     // Each wavefront owns 32 columns (64 bytes per row) but the four of a workgroup own 128
     // consecutive ones: all write into one [32 MU rows][256 bytes] image, one barrier, and every
     // store instruction then covers 4 full 256-byte row pieces.
-    const int w = tid >> 6;
     uint2* ep8 = reinterpret_cast<uint2*>(slab);
     if (has_n) {
 #pragma unroll
       for (int m = 0; m < MU; ++m) {
-        const int r = m * 32 + frow;
+        const int r = m * 32 + erow;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           bf16x4 o;
 #pragma unroll
           for (int j = 0; j < 4; ++j) o[j] = (__bf16)(silu(acc[0][m][q * 4 + j]) * acc[1][m][q * 4 + j]);
-          ep8[r * 32 + ((((w * 4 + q) ^ (r & 15)) << 1) | fg)] = __builtin_bit_cast(uint2, o);
+          ep8[r * 32 + ((((w * 4 + q) ^ (r & 15)) << 1) | eg)] = __builtin_bit_cast(uint2, o);
         }
       }
     }
     __syncthreads();
-    const int ru = lane & 15;
+    const int ru = elane & 15;
     const int col = (pair - w) * 32 + 8 * ru;      // columns of wavefronts past the last pair stay unwritten
     __bf16* cbase = C + (size_t)row0 * N + col;
 #pragma unroll
     for (int t = 0; t < 2 * MU; ++t) {
-      const int r = t * 16 + w * 4 + (lane >> 4);
+      const int r = t * 16 + w * 4 + (elane >> 4);
       const u32x4 v = slab[r * 16 + (ru ^ (r & 15))];
       if (r < rows && col < N) *reinterpret_cast<u32x4*>(cbase + (size_t)r * N) = v;
     }
@@ -556,9 +562,9 @@ __device__ __forceinline__ void wide_tile(const u32x4* __restrict__ X, const u32
     // at a time through a private 4 KiB piece of the slab. LDS operations of one wavefront execute
     // in order, so no barrier is needed.
     if (!has_n) return;
-    uint2* ep8 = reinterpret_cast<uint2*>(slab) + (tid >> 6) * 512;
-    const u32x4* ep16 = slab + (tid >> 6) * 256;
-    const int ru = lane & 7;
+    uint2* ep8 = reinterpret_cast<uint2*>(slab) + w * 512;
+    const u32x4* ep16 = slab + w * 256;
+    const int ru = elane & 7;
     __bf16* cbase = C + (size_t)row0 * N + pair * 64 + 8 * ru;
 #pragma unroll
     for (int m = 0; m < MU; ++m) {
@@ -569,12 +575,12 @@ __device__ __forceinline__ void wide_tile(const u32x4* __restrict__ X, const u32
           bf16x4 o;
 #pragma unroll
           for (int j = 0; j < 4; ++j) o[j] = (__bf16)acc[i][m][q * 4 + j];
-          ep8[frow * 16 + ((((i * 4 + q) ^ ((frow >> 1) & 7)) << 1) | fg)] = __builtin_bit_cast(uint2, o);
+          ep8[erow * 16 + ((((i * 4 + q) ^ ((erow >> 1) & 7)) << 1) | eg)] = __builtin_bit_cast(uint2, o);
         }
       }
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
-        const int r = t * 8 + (lane >> 3);         // row inside this 32-row group
+        const int r = t * 8 + (elane >> 3);         // row inside this 32-row group
         const u32x4 v = ep16[r * 8 + (ru ^ ((r >> 1) & 7))];
         if (m * 32 + r < rows) *reinterpret_cast<u32x4*>(cbase + (size_t)(m * 32 + r) * N) = v;
       }
@@ -613,7 +619,7 @@ __global__ __launch_bounds__(256) void ffn_bf16_wide_kernel(const u32x4* __restr
   static_for<1, kWideBM / 32 + 1>([&](auto mu_) {
     constexpr int MU = decltype(mu_)::value;
     if (mu == MU) {
-      if (once && MU <= 6) {  // (the 7- and 8-group variants have no registers left for it)
+      if (once) {
         if (MU <= 5 && deep) wide_tile<GATEUP, MU, 4, true>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
         else wide_tile<GATEUP, MU, 2, true>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
       } else {
@@ -813,12 +819,12 @@ hipError_t launch_ffn_segments(const moe_config& cfg, int stage, const int32_t* 
     if (stage == 0) {
       if (want <= 32.f) launch_bf16<1, 2, 2, 8, 1, true, true>(in, segs, w, out, A, N, K, stream);
       else if (want <= 64.f) launch_bf16<2, 2, 2, 8, 1, true, true>(in, segs, w, out, A, N, K, stream);
-      else if (stream128 || want <= wide_above) launch_bf16<4, 2, 2, 8, 1, true, true>(in, segs, w, out, A, N, K, stream);
+      else if (stream128 || want <= wide_above || K < 256) launch_bf16<4, 2, 2, 8, 1, true, true>(in, segs, w, out, A, N, K, stream);
       else launch_bf16_wide<true>(in, segs, w, out, A, rows_hint, N, K, stream);
     } else {
       if (want <= 32.f) launch_bf16<1, 1, 2, 8, 1, false, true>(in, segs, w, out, A, N, K, stream);
       else if (want <= 64.f) launch_bf16<2, 1, 2, 8, 1, false, true>(in, segs, w, out, A, N, K, stream);
-      else if (stream128 || want <= wide_above) launch_bf16<4, 1, 2, 8, 1, false, true>(in, segs, w, out, A, N, K, stream);
+      else if (stream128 || want <= wide_above || K < 256) launch_bf16<4, 1, 2, 8, 1, false, true>(in, segs, w, out, A, N, K, stream);
       else launch_bf16_wide<false>(in, segs, w, out, A, rows_hint, N, K, stream);
     }
     return hipGetLastError();
