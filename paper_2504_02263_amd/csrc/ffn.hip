@@ -395,9 +395,13 @@ __global__ __launch_bounds__(64 * WN * WM) void ffn_bf16_kernel(const u32x4* __r
 // reads buffer c % 3, takes the first fragments of chunk c + 1 from buffer (c + 1) % 3 before the
 // stage's barrier, and writes the tokens of chunk c + 2 into buffer (c + 2) % 3, so no MFMA waits
 // on LDS right after a barrier.
+// The tokens of chunk c + 2 are loaded from global memory TPF stages before the stage that stores
+// them: one stage for tall tiles, two for tiles of up to kWideTpf2Max row groups, whose stages are
+// shorter than an L2 round trip under load (and which have the registers for a second chunk in flight).
 constexpr int kWideBM = 256;
+constexpr int kWideTpf2Max = 5;
 
-template <bool GATEUP, int MU, int NST, bool NTL>
+template <bool GATEUP, int MU, int NST, bool NTL, int TPF>
 __device__ __forceinline__ void wide_tile(const u32x4* __restrict__ X, const u32x4* __restrict__ wbase,
                                           __bf16* __restrict__ C, u32x4* __restrict__ slab, int row0, int rows, int N,
                                           int K, int pair, bool has_n) {
@@ -418,18 +422,18 @@ __device__ __forceinline__ void wide_tile(const u32x4* __restrict__ X, const u32
   for (int s = 0; s < 4; ++s) rd[s] = frow * 8 + ((2 * s + fg) ^ ((frow >> 1) & 7));
 
   u32x4 wreg[NST][8];
-  u32x4 treg[MU];
+  u32x4 treg[TPF][MU];  // token chunks in flight, loaded TPF stages before they go to LDS
   bf16x8 bfr[R];
   floatx16 acc[2][MU];
 
-  auto load_t = [&](int c) {
+  auto load_t = [&](auto slot_, int c) {
     c = min(c, NC - 1);
 #pragma unroll
-    for (int p = 0; p < MU; ++p) treg[p] = xrow[p][c * 8];
+    for (int p = 0; p < MU; ++p) treg[decltype(slot_)::value][p] = xrow[p][c * 8];
   };
-  auto store_t = [&](int boff) {
+  auto store_t = [&](auto slot_, int boff) {
 #pragma unroll
-    for (int p = 0; p < MU; ++p) slab[boff + p * 256 + swz_w] = treg[p];
+    for (int p = 0; p < MU; ++p) slab[boff + p * 256 + swz_w] = treg[decltype(slot_)::value][p];
   };
   auto load_w_step = [&](auto st_, int c, int s) {
     constexpr int st = decltype(st_)::value;
@@ -443,9 +447,9 @@ __device__ __forceinline__ void wide_tile(const u32x4* __restrict__ X, const u32
     return __builtin_bit_cast(bf16x8, slab[boff + (it % MU) * 256 + rd[it / MU]]);
   };
 
-  // prologue: all first loads go out at once (tokens of chunks 0, 1, 2, then the weights of the first
-  // NST chunks), so the workgroup pays one memory latency before its first MFMA; chunks 0 and 1 go
-  // to LDS, chunk 2 stays in registers for stage 0
+  // prologue: all first loads go out at once (tokens of chunks 0 .. 1 + TPF, then the weights of the
+  // first NST chunks), so the workgroup pays one memory latency before its first MFMA; chunks 0 and 1
+  // go to LDS, chunk 2 (and 3) stay in registers for stage 0 (and 1)
   {
     u32x4 t0[MU], t1[MU];
 #pragma unroll
@@ -453,7 +457,11 @@ __device__ __forceinline__ void wide_tile(const u32x4* __restrict__ X, const u32
 #pragma unroll
     for (int p = 0; p < MU; ++p) t1[p] = xrow[p][8];
 #pragma unroll
-    for (int p = 0; p < MU; ++p) treg[p] = xrow[p][16];  // K >= 256 (the launcher sees to it): chunks 1, 2 exist
+    for (int p = 0; p < MU; ++p) treg[0][p] = xrow[p][16];  // K >= 256 (the launcher sees to it): chunks 1..3 exist
+    if constexpr (TPF == 2) {
+#pragma unroll
+      for (int p = 0; p < MU; ++p) treg[1][p] = xrow[p][24];
+    }
     static_for<0, NST>([&](auto st_) {
 #pragma unroll
       for (int s = 0; s < 4; ++s) load_w_step(st_, decltype(st_)::value, s);
@@ -492,8 +500,8 @@ __device__ __forceinline__ void wide_tile(const u32x4* __restrict__ X, const u32
       if (s == 0) {
         // token loads go out before this stage's weight loads: loads return in order, and waiting
         // for these tokens one stage from now must not wait for weights needed NST stages from now
-        store_t(wr);  // tokens of chunk c + 2
-        load_t(c + 3);
+        store_t(std::integral_constant<int, st % TPF>{}, wr);  // tokens of chunk c + 2
+        load_t(std::integral_constant<int, st % TPF>{}, c + 2 + TPF);
       }
       load_w_step(st_, c + NST, s);  // this k-step's weight registers are free again
 #pragma unroll
@@ -618,13 +626,14 @@ __global__ __launch_bounds__(256) void ffn_bf16_wide_kernel(const u32x4* __restr
   const bool once = loc.tiles == 1;
   static_for<1, kWideBM / 32 + 1>([&](auto mu_) {
     constexpr int MU = decltype(mu_)::value;
+    constexpr int TPF = MU <= kWideTpf2Max ? 2 : 1;  // short stages: token loads go out two stages ahead
     if (mu == MU) {
       if (once) {
-        if (MU <= 5 && deep) wide_tile<GATEUP, MU, 4, true>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
-        else wide_tile<GATEUP, MU, 2, true>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
+        if (MU <= 5 && deep) wide_tile<GATEUP, MU, 4, true, TPF>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
+        else wide_tile<GATEUP, MU, 2, true, TPF>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
       } else {
-        if (MU <= 5 && deep) wide_tile<GATEUP, MU, 4, false>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
-        else wide_tile<GATEUP, MU, 2, false>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
+        if (MU <= 5 && deep) wide_tile<GATEUP, MU, 4, false, TPF>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
+        else wide_tile<GATEUP, MU, 2, false, TPF>(X, wbase, C, slab, loc.row0, rows, N, K, pair, has_n);
       }
     }
   });
