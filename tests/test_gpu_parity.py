@@ -490,3 +490,32 @@ def test_seeded_random_layers(T, d, f, E, k, dtype, skew):
     err = rel_fro(host(path.out)[:T], ref["out"])
     assert err <= TOL[dtype], (cfg.name, err)
     path.close()
+
+
+def _random_large_batch_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        E = int(rng.choice([1, 2, 3, 4, 6, 8, 16]))
+        k = int(rng.integers(1, min(E, 4) + 1))
+        cases.append((int(rng.choice([900, 1500, 2222, 3000, 4097])), 128 * int(rng.integers(2, 7)),
+                      128 * int(rng.integers(2, 9)), E, k, float(rng.choice([0.0, 0.5, 1.0, 2.0]))))
+    return cases
+
+
+@pytest.mark.parametrize("T,d,f,E,k,skew", _random_large_batch_cases(16, 77))
+def test_seeded_random_large_batch_layers(T, d, f, E, k, skew):
+    """The same sweep at hundreds to thousands of rows per expert: every tile height of the large-batch kernel,
+    experts split over several tiles, both orders of the tile queue, K from 256 to 1024."""
+    cfg = small_cfg(T, d, f, E, k, "bf16")
+    x = synth.make_activations(cfg, 32)
+    logits = synth.make_logits(cfg, 32)
+    if skew:
+        logits = (logits - skew * np.log(np.arange(1, E + 1, dtype=np.float32))).astype(np.float32)
+    W = synth.make_all_expert_weights(cfg, 32, workers=4)
+    ref = O.moe_layer(x, logits, k, lambda e: (W[0][e], W[1][e], W[2][e]))
+    path = run_layer(cfg, x, logits, W)
+    check_integers(path, ref, T, k)
+    err = rel_fro(host(path.out)[:T], ref["out"])
+    assert err <= TOL["bf16"], (cfg.name, err)
+    path.close()
