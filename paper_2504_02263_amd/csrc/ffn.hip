@@ -809,31 +809,31 @@ hipError_t launch_ffn_segments(const moe_config& cfg, int stage, const int32_t* 
   const size_t one = (size_t)cfg.E * cfg.d * cfg.f;  // elements of one matrix set
   const int N = stage == 0 ? cfg.f : cfg.d, K = stage == 0 ? cfg.d : cfg.f;
   if (cfg.dtype == MOE_BF16) {
-    // The host never sees the per-segment row counts, so the tile shape comes from the mean rows
-    // per segment: mean + 3 sqrt(mean) covers the spread of a near-uniform router, so most experts
-    // fit one m-tile. Up to 128 rows: 8 wavefronts side by side along N, weights streamed once
-    // (non-temporal). Above: the 256-row matrix-core-bound kernel, weights shared through L2.
+    // The host never sees the per-segment row counts, so the kernel comes from the mean rows per
+    // segment. Up to mean + 2 sigma <= 128 (sigma = sqrt(mean), the spread of a near-uniform router):
+    // the streaming kernel, 8 wavefronts side by side along N, weights read once (non-temporal). Its
+    // tiles are always 128 rows tall: a wavefront only computes the 32-row groups that hold real rows,
+    // so at 8 rows per expert the tall tile costs nothing (measured: +-0.5 % against 32- or 64-row
+    // tiles), while under a skewed router the popular experts still fit one tile and their weights
+    // are read once (a Zipf load of 2...54 rows per expert: 15 % faster than with 32-row tiles). A few
+    // experts may need a second, short tile, which costs less than leaving the streaming kernel
+    // (measured at 104 and 112 mean rows: 3 % faster; at 120 mean rows the large-batch kernel wins).
+    // Above: the 256-row matrix-core-bound kernel, weights shared through L2; it needs K >= 256.
     const float mean = (float)rows_hint / n_segs;
     const float want = mean + 3.f * sqrtf(mean);
-    // The last step of the streaming kernel (128-row tiles) is kept up to mean + 2 sigma <= 128: a few
-    // experts may then need a second, short tile, which costs less than leaving the streaming kernel
-    // (measured at 104 and 112 mean rows: 3 % faster; at 120 mean rows the large-batch kernel wins).
     const bool stream128 = mean + 2.f * sqrtf(mean) <= 128.f;
     // Tuning knob (read once): MOE_FFN_WIDE_ABOVE=<rows> moves the switch-over between the two kernels.
     static const float wide_above = [] {
       const char* v = getenv("MOE_FFN_WIDE_ABOVE");
       return v ? (float)atof(v) : 128.f;
     }();
+    const bool streaming = stream128 || want <= wide_above || K < 256;
     const char* w = static_cast<const char*>(packed) + (stage == 0 ? 0 : 2 * one * 2);
     if (stage == 0) {
-      if (want <= 32.f) launch_bf16<1, 2, 2, 8, 1, true, true>(in, segs, w, out, A, N, K, stream);
-      else if (want <= 64.f) launch_bf16<2, 2, 2, 8, 1, true, true>(in, segs, w, out, A, N, K, stream);
-      else if (stream128 || want <= wide_above || K < 256) launch_bf16<4, 2, 2, 8, 1, true, true>(in, segs, w, out, A, N, K, stream);
+      if (streaming) launch_bf16<4, 2, 2, 8, 1, true, true>(in, segs, w, out, A, N, K, stream);
       else launch_bf16_wide<true>(in, segs, w, out, A, rows_hint, N, K, stream);
     } else {
-      if (want <= 32.f) launch_bf16<1, 1, 2, 8, 1, false, true>(in, segs, w, out, A, N, K, stream);
-      else if (want <= 64.f) launch_bf16<2, 1, 2, 8, 1, false, true>(in, segs, w, out, A, N, K, stream);
-      else if (stream128 || want <= wide_above || K < 256) launch_bf16<4, 1, 2, 8, 1, false, true>(in, segs, w, out, A, N, K, stream);
+      if (streaming) launch_bf16<4, 1, 2, 8, 1, false, true>(in, segs, w, out, A, N, K, stream);
       else launch_bf16_wide<false>(in, segs, w, out, A, rows_hint, N, K, stream);
     }
     return hipGetLastError();
