@@ -819,7 +819,14 @@ hipError_t launch_ffn_segments(const moe_config& cfg, int stage, const int32_t* 
     // experts may need a second, short tile, which costs less than leaving the streaming kernel
     // (measured at 104 and 112 mean rows: 3 % faster; at 120 mean rows the large-batch kernel wins).
     // Above: the 256-row matrix-core-bound kernel, weights shared through L2; it needs K >= 256.
-    const float mean = (float)rows_hint / n_segs;
+    // Tuning knob (read once): MOE_FFN_LOAD_SKEW=<ratio> tells the choice how many times the mean the
+    // popular segments hold (a serving engine knows that from recent traffic; default 1 = uniform).
+    static const float skew = [] {
+      const char* v = getenv("MOE_FFN_LOAD_SKEW");
+      const float r = v ? (float)atof(v) : 1.f;
+      return r >= 1.f ? r : 1.f;
+    }();
+    const float mean = skew * (float)rows_hint / n_segs;
     const float want = mean + 3.f * sqrtf(mean);
     const bool stream128 = mean + 2.f * sqrtf(mean) <= 128.f;
     // Tuning knob (read once): MOE_FFN_WIDE_ABOVE=<rows> moves the switch-over between the two kernels.
