@@ -359,6 +359,29 @@ def test_expert_ffn_equals_its_two_stages_and_is_deterministic():
     path.close()
 
 
+@pytest.mark.parametrize("T,d,f,E,k", [(1500, 256, 384, 4, 2), (3000, 512, 256, 6, 3), (900, 384, 1024, 3, 1)])
+def test_both_gemm_kernels_give_the_same_bits(T, d, f, E, k):
+    """Which GEMM kernel runs is a host-side guess from the mean rows per segment (and environment knobs). Both
+    accumulate K in the same order with the same matrix-core instruction, so the guess must never show in a
+    result: the same rows through the streaming kernel (small rows hint) and the large-batch kernel (true hint)."""
+    cfg = small_cfg(T, d, f, E, k, "bf16")
+    x, logits = synth.make_activations(cfg, 3), synth.make_logits(cfg, 3)
+    W = synth.make_all_expert_weights(cfg, 3, workers=4)
+    path = run_layer(cfg, x, logits, W)
+    A = T * k
+    seg_e = torch.arange(E, dtype=torch.int32, device="cuda")
+    beg, end = path.offsets[:E].clone(), path.offsets[1:E + 1].clone()
+    got = []
+    for hint in (8 * E, A):
+        path.h.zero_()
+        path.y.zero_()
+        B.moe_expert_ffn_segments(path.ctx, T, E, hint, path.xp, beg, end, seg_e, path.packed, path.h, path.y)
+        torch.cuda.synchronize()
+        got.append((host(path.h)[:A].copy(), host(path.y)[:A].copy()))
+    assert (got[0][0] == got[1][0]).all() and (got[0][1] == got[1][1]).all()
+    path.close()
+
+
 def test_all_tokens_to_one_expert():
     """Degenerate routing: every token picks the same experts (k = 2 of 4), so two segments hold
     all rows and two are empty."""
