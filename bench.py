@@ -216,6 +216,47 @@ def expert_plan_experiment(cfg, path, x_d, logits_d, N, S, B, torch, reps=10):
             "max_node_time_ratio_greedy_over_plain": round(max(plan_t) / max(plain_t), 3)}
 
 
+def per_expert_breakdown(cfg, path, x_d, logits_d, B, R, torch, reps=10):
+    """Every expert's own rows through both FFN GEMMs, timed alone (one segment per call): rows, time,
+    rates, and which roof of the paper's model (Section 2.3) the expert sits under on this chip. The
+    sum over experts exceeds the fused launch, where experts overlap and share the chip."""
+    T, E = cfg.T, cfg.E
+    path.route(logits_d, T)
+    path.dispatch(x_d, T)
+    torch.cuda.synchronize()
+    counts = path.counts.cpu().tolist()
+    offsets = path.offsets.cpu().tolist()
+    s = 2 if cfg.dtype == "bf16" else 4
+    ridge = R.ridge_batch(R.MI355X_BF16_DENSE_FLOPS, R.MI355X_HBM_BYTES_PER_S)
+    i32 = torch.int32
+    rows_out = []
+    for e in range(E):
+        c = counts[e]
+        if c == 0:
+            rows_out.append({"expert": e, "rows": 0})
+            continue
+        b = torch.full((1,), offsets[e], dtype=i32, device="cuda")
+        en = torch.full((1,), offsets[e + 1], dtype=i32, device="cuda")
+        ex = torch.full((1,), e, dtype=i32, device="cuda")
+        call = lambda: B.moe_expert_ffn_segments(path.ctx, T, 1, c, path.xp, b, en, ex, path.packed, path.h, path.y)
+        call()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        flops = 6.0 * c * cfg.d * cfg.f
+        nbytes = 3.0 * cfg.d * cfg.f * s + c * (2 * cfg.d + 2 * cfg.f) * s
+        rows_out.append({"expert": e, "rows": c, "ms": round(ms, 4), "TFLOP/s": round(flops / ms / 1e9, 1),
+                         "GB/s": round(nbytes / ms / 1e6, 1), "roof": "hbm" if c < ridge else "mfma"})
+    alone = sum(r.get("ms", 0.0) for r in rows_out)
+    return {"per_expert": cfg.name, "ridge_rows": round(ridge, 1), "experts": rows_out,
+            "sum_of_experts_alone_ms": round(alone, 4)}
+
+
 def measure_ceilings(path, B, torch, reps=5):
     """What this chip reaches for the roofline's two denominators, measured beside the layer: a plain
     streaming read of the packed weights, and matrix-core issue from registers with real weight bits as
@@ -385,6 +426,8 @@ def main():
     ap.add_argument("--expert-plan", default="", metavar="N,S",
                     help="also time every node's share of the expert FFN for N expert nodes, plain deployment "
                          "against the greedy plan with S slots per node (hot experts get copies)")
+    ap.add_argument("--per-expert", action="store_true",
+                    help="also time every expert's own rows alone (both FFN GEMMs) and print rows, time, rates and roof")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--vendor-gemm", action="store_true",
                     help="also time the vendor GEMM library on the two expert GEMMs of this workload (one call per "
@@ -474,6 +517,14 @@ def main():
         y = vendor_gemm_yardstick(cfg, torch)
         y["this_library_ms"] = {n: lines[-1]["layer"]["calls_ms"][n] for n in ("ffn_input", "ffn_output")}
         print(json.dumps(y), flush=True)
+    if args.per_expert:
+        x, logits = make_inputs(cfg, args.seed, synth)
+        a0, b0 = synth.microbatch_ranges(cfg.T, cfg.micro_batches)[0]     # the first micro-batch stands for the others
+        from dataclasses import replace as _replace
+        pe = per_expert_breakdown(_replace(cfg, T=b0 - a0), paths[0], dev(x[a0:b0], torch), dev(logits[a0:b0], torch),
+                                  B, R, torch)
+        pe["fused_launches_ms"] = round(lines[-1]["layer"]["calls_ms"]["ffn_input"] + lines[-1]["layer"]["calls_ms"]["ffn_output"], 4)
+        print(json.dumps(pe), flush=True)
     if args.expert_plan:
         N, S = (int(v) for v in args.expert_plan.split(","))
         if cfg.E % N or N * S < cfg.E:
