@@ -43,11 +43,13 @@ _lib = None
 
 
 def load_library() -> ctypes.CDLL:
-    """Load libmoe_gfx950.so (building it first only if no built library exists)."""
+    """Load libmoe_gfx950.so. It is built first if no built library exists or if the one that
+    exists was built from other sources than the tree holds now (build.py keeps a hash of the
+    sources beside the library), so an edited kernel never runs from a stale binary."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.LIB_PATH):
+    if not _build.is_current():
         _build.build()
     lib = ctypes.CDLL(_build.LIB_PATH)
     vp, i32, cfgp = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(MoeConfig)
