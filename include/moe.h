@@ -143,6 +143,22 @@ moe_status moe_expert_ffn(moe_ctx* ctx, int32_t T, const void* xp, const int32_t
                           const void* packed_w, void* h_ws, void* y, void* stream);
 
 /*
+ * moe_expert_ffn without a caller-provided workspace, for callers that cannot allocate device
+ * memory: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc. The
+ * intermediate h[T*k, f] lives in a static array of MOE_STATIC_SCRATCH_BYTES inside the library's
+ * device image (every GPU the library runs on holds its own copy until the process ends); the call
+ * allocates and frees nothing. Same kernels and the same y, bit for bit, as moe_expert_ffn.
+ * MOE_ERR_UNSUPPORTED (nothing launched, y untouched) if T*k*f*sizeof(element) exceeds
+ * MOE_STATIC_SCRATCH_BYTES. All calls on one GPU share that GPU's array: calls that overlap in time
+ * on one GPU (different streams, or different contexts) race on h; issue them on one stream or
+ * order them with events. Nothing in the array has to start at zero (every row of h that is read
+ * was written by the same call before).
+ */
+#define MOE_STATIC_SCRATCH_BYTES (64u << 20)
+moe_status moe_expert_ffn_static(moe_ctx* ctx, int32_t T, const void* xp, const int32_t* offsets,
+                                 const void* packed_w, void* y, void* stream);
+
+/*
  * The two GEMM stages of moe_expert_ffn as separate calls, named as in Table 3 (same kernels,
  * same results; moe_expert_ffn is moe_ffn_input followed by moe_ffn_output):
  *   moe_ffn_input :  h[A, f] = silu(xp * W_gate^T) .* (xp * W_up^T)     reads xp[A, d]

@@ -25,7 +25,7 @@ _DTYPES = {"f32": (MOE_F32, torch.float32), "bf16": (MOE_BF16, torch.bfloat16)}
 EXPORTS = ("moe_create", "moe_destroy", "moe_last_error", "moe_status_string", "moe_packed_weight_bytes",
            "moe_pack_weights", "moe_route", "moe_gate_route", "moe_dispatch", "moe_expert_ffn", "moe_ffn_input", "moe_ffn_output",
            "moe_combine", "moe_plan_experts", "moe_slot_segments", "moe_expert_ffn_segments", "moe_route_dispatch",
-           "moe_probe_stream_read", "moe_probe_mfma")
+           "moe_expert_ffn_static", "moe_probe_stream_read", "moe_probe_mfma")
 
 
 class MoeConfig(ctypes.Structure):
@@ -69,6 +69,8 @@ def load_library() -> ctypes.CDLL:
     lib.moe_dispatch.argtypes = [vp, i32] + [vp] * 6 + [vp]
     lib.moe_route_dispatch.argtypes = [vp, i32] + [vp] * 9 + [vp]
     lib.moe_expert_ffn.argtypes = [vp, i32] + [vp] * 5 + [vp]
+    lib.moe_expert_ffn_static.argtypes = [vp, i32] + [vp] * 4 + [vp]
+    lib.moe_expert_ffn_static.restype = ctypes.c_int
     lib.moe_ffn_input.argtypes = [vp, i32] + [vp] * 4 + [vp]
     lib.moe_ffn_output.argtypes = [vp, i32] + [vp] * 4 + [vp]
     lib.moe_combine.argtypes = [vp, i32] + [vp] * 4 + [vp]
@@ -158,6 +160,11 @@ def moe_route_dispatch(ctx, T, logits, x, topk_idx, topk_w, counts, offsets, xp,
 def moe_expert_ffn(ctx, T, xp, offsets, packed_w, h_ws, y, stream=None) -> None:
     _check(ctx, load_library().moe_expert_ffn(ctx, T, _ptr(xp), _ptr(offsets), _ptr(packed_w), _ptr(h_ws), _ptr(y),
                                               _stream(stream)))
+
+
+def moe_expert_ffn_static(ctx, T, xp, offsets, packed_w, y, stream=None) -> None:
+    _check(ctx, load_library().moe_expert_ffn_static(ctx, T, _ptr(xp), _ptr(offsets), _ptr(packed_w), _ptr(y),
+                                                     _stream(stream)))
 
 
 def moe_ffn_input(ctx, T, xp, offsets, packed_w, h, stream=None) -> None:

@@ -2,10 +2,40 @@
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
+#include <mutex>
 #include <new>
 #include "moe_internal.h"
 
+// Workspace of moe_expert_ffn_static: the intermediate h[A, f] of the two-stage expert FFN, held in
+// the library's own device image so that the call allocates nothing. Every GPU the library runs on
+// holds its own copy of this array, at its own address, until the process ends. In host code the
+// name below is only a handle for hipGetSymbolAddress; kernels are given the address it returns.
+static __device__ __align__(256) unsigned char scratch[MOE_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each GPU, once resolved
+
+// Device address of `scratch` on the current device (resolved once per device, with that device
+// current). Allocates nothing: the array is part of the loaded code object.
+hipError_t static_scratch(void** out) {
+  int dev = -1;
+  hipError_t err = hipGetDevice(&dev);
+  if (err != hipSuccess) return err;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (err != hipSuccess) return err;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
 
 moe_status fail(moe_ctx* ctx, moe_status s, const char* fmt, ...) {
   if (ctx) {
@@ -69,6 +99,15 @@ moe_status moe_create(const moe_config* cfg, moe_ctx** out) {
   if (!ctx) return MOE_ERR_INVALID_ARG;
   ctx->cfg = *cfg;
   ctx->err[0] = 0;
+  // Where a GPU is present, find the static workspace of moe_expert_ffn_static on the current device
+  // now, so that the hot call has nothing left to set up. Best effort: a host without a GPU can still
+  // create contexts (argument checks, the planner), and the hot call resolves it on first use otherwise.
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) == hipSuccess && n_dev > 0) {
+    void* p = nullptr;
+    (void)static_scratch(&p);
+  }
+  (void)hipGetLastError();
   *out = ctx;
   return MOE_OK;
 }
@@ -177,6 +216,26 @@ moe_status moe_expert_ffn(moe_ctx* ctx, int32_t T, const void* xp, const int32_t
   if (err == hipSuccess)
     err = moe::launch_ffn_stage(ctx->cfg, 1, T, h_ws, offsets, packed_w, y, static_cast<hipStream_t>(stream));
   return finish(ctx, "moe_expert_ffn", err);
+}
+
+moe_status moe_expert_ffn_static(moe_ctx* ctx, int32_t T, const void* xp, const int32_t* offsets, const void* packed_w,
+                                 void* y, void* stream) {
+  const void* ptrs[] = {xp, offsets, packed_w, y};
+  const moe_status s = check_call(ctx, "moe_expert_ffn_static", T, ptrs, 4);
+  if (s != MOE_OK) return s;
+  const size_t need = (size_t)T * ctx->cfg.k * ctx->cfg.f * elem_bytes(ctx);
+  if (need > (size_t)MOE_STATIC_SCRATCH_BYTES)
+    return fail(ctx, MOE_ERR_UNSUPPORTED,
+                "moe_expert_ffn_static: h[T*k, f] needs %zu bytes, the static workspace holds %zu; use moe_expert_ffn",
+                need, (size_t)MOE_STATIC_SCRATCH_BYTES);
+  if (T == 0) return MOE_OK;
+  void* h_ws = nullptr;
+  hipError_t err = static_scratch(&h_ws);
+  if (err == hipSuccess)
+    err = moe::launch_ffn_stage(ctx->cfg, 0, T, xp, offsets, packed_w, h_ws, static_cast<hipStream_t>(stream));
+  if (err == hipSuccess)
+    err = moe::launch_ffn_stage(ctx->cfg, 1, T, h_ws, offsets, packed_w, y, static_cast<hipStream_t>(stream));
+  return finish(ctx, "moe_expert_ffn_static", err);
 }
 
 moe_status moe_slot_segments(moe_ctx* ctx, int32_t n_slots, const int32_t* slot_expert, const int32_t* slot_copy,
