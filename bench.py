@@ -6,12 +6,20 @@ A step is one pass of the whole path (moe_route_dispatch [= moe_route, moe_dispa
 default workload is the Mixtral-8x22B-shaped decode micro-batch (d=6144, f=16384, E=8, top-2,
 bf16, T=256), the configuration the headline metric is quoted on.
 
-Prints ONE JSON line. `roofline` is for the dominant kernel
-(the fused gate|up "FFN Input" GEMM): algorithmic bytes or flops per launch over its average
-duration, measured with events on the launch stream inside the timed region. `cpu_baseline` is
-the CPU oracle, as it stands, timed on this machine's host cores on a bounded sample.
+Prints ONE JSON line. `value`, `ms_per_step` and `roofline` belong to `config.workload`. `roofline`
+is for the dominant kernel (the fused gate|up "FFN Input" GEMM): algorithmic bytes or flops per
+launch over its average duration, measured with events on the launch stream inside the timed
+region. `cpu_baseline` is the CPU oracle, as it stands, timed on this machine's host cores on a
+bounded sample.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--sweep] [--no-cpu-baseline]
+The metric is a curve over the per-expert batch, so the default run (no --workload) also times the
+same layer at T = 32 ... 4096 on the same weights, each point with the same W warm-up and K timed
+steps, and carries them in `sweep` (`roofline_large_batch` repeats the FFN-input roofline of the
+largest point, the matrix-core-bound end), and it times the fine-grained many-expert layer cut into
+m = 1 ... 4 micro-batches on two alternating streams (`micro_batch_study`).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]            # headline + sweep + micro-batch study
+    python bench.py --workload NAME [--sweep] [--no-cpu-baseline]  # one workload (profiles are taken this way)
 """
 from __future__ import annotations
 
@@ -34,8 +42,9 @@ def dev(a, torch):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def upload_and_pack(cfg, seed, path, torch, synth):
-    """Generate the expert weights on the host, upload, pre-pack once (outside any timed region)."""
+def upload_and_pack(cfg, seed, path, torch, synth, keep=True):
+    """Generate the expert weights on the host, upload, pre-pack once (outside any timed region).
+    keep=False drops the host copy (it is only needed where the CPU oracle runs on the same weights)."""
     t0 = time.time()
     W = synth.make_all_expert_weights(cfg, seed, workers=min(16, os.cpu_count() or 8))
     gen_s = time.time() - t0
@@ -44,7 +53,7 @@ def upload_and_pack(cfg, seed, path, torch, synth):
     torch.cuda.synchronize()
     del wg, wu, wd
     torch.cuda.empty_cache()
-    return W, gen_s
+    return (W if keep else None), gen_s
 
 
 def make_inputs(cfg, seed, synth):
@@ -56,7 +65,7 @@ def make_inputs(cfg, seed, synth):
 kSettleSeconds = 0.3
 
 
-def time_workload(cfg, paths, x_d, logits_d, steps, warmup, torch, R, synth):
+def time_workload(cfg, paths, x_d, logits_d, steps, warmup, torch, R, synth, breakdown=True):
     """W warm-up steps, then exactly K timed steps between device synchronisations.
 
     A step runs the whole path over the batch. With cfg.micro_batches = m > 1 the batch is cut
@@ -128,7 +137,7 @@ def time_workload(cfg, paths, x_d, logits_d, steps, warmup, torch, R, synth):
     calls = [lambda: path.route(logits_d[a:b], T, stream), lambda: path.dispatch(x_d[a:b], T, stream),
              lambda: path.route_dispatch(x_d[a:b], logits_d[a:b], T, stream),
              lambda: path.ffn_input(T, stream), lambda: path.ffn_output(T, stream), lambda: path.combine(T, stream)]
-    reps = max(5, min(steps, 20))
+    reps = max(5, min(steps, 20)) if breakdown else 0
     acc = {n: [] for n in names}
     for _ in range(reps):
         evs = [torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)]
@@ -139,7 +148,7 @@ def time_workload(cfg, paths, x_d, logits_d, steps, warmup, torch, R, synth):
         sync()
         for i, n in enumerate(names):
             acc[n].append(evs[i].elapsed_time(evs[i + 1]))
-    calls_ms = {n: float(np.median(v)) for n, v in acc.items()}
+    calls_ms = {n: float(np.median(v)) if v else None for n, v in acc.items()}
 
     counts = path.counts.cpu().numpy()          # of the first micro-batch
     active = int((counts > 0).sum())
@@ -285,39 +294,6 @@ def measure_ceilings(path, B, torch, reps=5):
     return out
 
 
-def vendor_gemm_yardstick(cfg, torch, reps=10):
-    """The vendor GEMM library (torch.matmul into preallocated outputs) on the same job as the two expert
-    GEMMs: one call per expert, distinct random weights, uniform rows per expert, nothing fused. A yardstick
-    printed beside the result, not part of the path."""
-    E, d, f = cfg.E, cfg.d, cfg.f
-    M = max(1, cfg.T * cfg.k // E // cfg.micro_batches)
-    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
-    out = {"vendor_gemm": f"{E} calls per stage, {M} rows each", "note": "torch.matmul, random data, no activation fused"}
-    for name, N, K in (("ffn_input", 2 * f, d), ("ffn_output", d, f)):
-        a = [torch.randn(M, K, device="cuda").to(dt) for _ in range(E)]
-        b = [(torch.randn(N, K, device="cuda") * K ** -0.5).to(dt) for _ in range(E)]
-        c = [torch.empty(M, N, device="cuda", dtype=dt) for _ in range(E)]
-
-        def step():
-            for e in range(E):
-                torch.matmul(a[e], b[e].t(), out=c[e])
-        for _ in range(3):
-            step()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            step()
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / reps
-        out[name] = {"ms": round(ms, 4), "TFLOP/s": round(2.0 * E * M * N * K / (ms * 1e-3) / 1e12, 1),
-                     "weight_GB/s": round(E * N * K * (2 if cfg.dtype == "bf16" else 4) / (ms * 1e-3) / 1e9, 1)}
-        del a, b, c
-        torch.cuda.empty_cache()
-    return out
-
-
 def roofline_entry(cfg, cost, ffn_in_ms, R):
     t = ffn_in_ms * 1e-3
     if cfg.dtype == "bf16":
@@ -331,15 +307,19 @@ def roofline_entry(cfg, cost, ffn_in_ms, R):
     else:
         achieved, peak, unit = cost.ffn_in_flops / t / 1e12, peak_flops / 1e12, unit_f
         bound = "mfma" if cfg.dtype == "bf16" else "alu"
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"traffic_{cfg.name}.json")
-    if os.path.exists(tpath):
+    # `traffic` cannot be measured inside this process (it needs the profiler's counters): it is the
+    # stored result of the rocprofv3 --pmc runs of this workload, and is labelled as such.
+    traffic, source = None, None
+    rel = f"profiles/traffic_{cfg.name}.json"
+    if os.path.exists(os.path.join(ROOT, rel)):
         try:
-            traffic = json.load(open(tpath)).get("ffn_input_hbm_bytes_per_launch")
+            traffic = json.load(open(os.path.join(ROOT, rel))).get("ffn_input_hbm_bytes_per_launch")
+            source = f"{rel} (stored from earlier rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs; not measured in this run)"
         except Exception:
             traffic = None
     return {"kernel": "ffn_input (fused gate|up GEMM + SiLU*up)", "bound": bound, "achieved": round(achieved, 2),
             "peak": peak, "unit": unit, "frac": round(achieved / peak, 4), "traffic": traffic,
+            "traffic_source": source,
             "algorithmic_bytes": cost.ffn_in_bytes, "algorithmic_flops": cost.ffn_in_flops,
             "avg_launch_ms": round(ffn_in_ms, 5)}
 
@@ -347,18 +327,21 @@ def roofline_entry(cfg, cost, ffn_in_ms, R):
 def cpu_baseline(cfg, seed, W, x, logits, oracle_mod, sample_tokens):
     """The oracle's whole layer on the first `sample_tokens` tokens of the same batch."""
     n = min(sample_tokens, cfg.T)
+    affinity = len(os.sched_getaffinity(0))
     try:
         from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        pools = [p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"]
+        threads, source = max(pools), "threadpoolctl: threads of the BLAS pool numpy's matmul runs on"
     except Exception:
-        threads = 1
+        threads, source = affinity, "sched_getaffinity (the BLAS pool could not be queried)"
     t0 = time.perf_counter()
     oracle_mod.moe_layer(x[:n], logits[:n], cfg.k, lambda e: (W[0][e], W[1][e], W[2][e]))
     dt = time.perf_counter() - t0
     return {"value": round(n / dt, 3), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
             "sample": f"whole layer (route, dispatch, expert FFN, combine) on the first {n} of {cfg.T} tokens, "
                       f"float64 numpy, {dt:.1f} s",
-            "host_cpus": os.cpu_count()}
+            "gflops": round(6.0 * n * cfg.k * cfg.d * cfg.f / dt / 1e9, 1),
+            "cores_source": source, "sched_getaffinity_cpus": affinity, "host_cpus": os.cpu_count()}
 
 
 def per_call_rates(cfg, r, R):
@@ -411,27 +394,80 @@ def result_line(cfg, steps, warmup, r, R, cpu, ceilings=None):
     return line
 
 
+def sweep_entry(line):
+    """One point of the curve `sweep` carries: what the per-expert batch was, what the step cost, and
+    where the FFN-input GEMM sits against its roofline."""
+    c, rf, lay = line["config"], line["roofline"], line["layer"]
+    return {"workload": c["workload"], "T": c["T"], "tokens_per_expert_mean": c["tokens_per_expert_mean"],
+            "tokens_per_expert_min": c["tokens_per_expert_min"], "tokens_per_expert_max": c["tokens_per_expert_max"],
+            "ms_per_step": line["ms_per_step"], "tokens_per_s": line["value"], "layer_tflops": lay["tflops"],
+            "ffn_kernel": c.get("ffn_kernel"),
+            "ffn_input": {k: rf[k] for k in ("bound", "achieved", "peak", "unit", "frac", "avg_launch_ms")},
+            "ffn_output_ms": lay["calls_ms"]["ffn_output"],
+            "layer_hbm_frac_of_min_bytes": lay["hbm_frac_of_min_bytes"], "layer_mfma_frac": lay["mfma_frac"]}
+
+
+def resolve_workload(name, synth):
+    if name in synth.CONFIGS:
+        return synth.CONFIGS[name]
+    if "_T" in name and any(n.startswith(name.split("_T")[0] + "_T") for n in synth.CONFIGS):
+        base, T = name.split("_T")          # a named shape at another token count, e.g. mixtral_T1024
+        return next(c for n, c in synth.CONFIGS.items() if n.startswith(base + "_T")).with_T(int(T))
+    raise SystemExit(f"unknown workload {name!r}; known: {sorted(synth.CONFIGS)}, or one of these shapes at "
+                     f"another token count (<shape>_T<N>)")
+
+
+def micro_batch_study(args, torch, B, R, synth, ms=(1, 2, 3, 4)):
+    """The fine-grained many-expert layer (8192 tokens) cut into m micro-batches on two alternating streams
+    (the single-GPU echo of the paper's ping-pong micro-batching, Section 4.1, whose m is capped at 4 because
+    smaller micro-batches lower GEMM efficiency, Section 4.2): ms per step on two streams and on one."""
+    from dataclasses import replace
+    base = synth.CONFIGS["finegrained_T8192"]
+    paths = [B.MoEPath(base.T, base.d, base.f, base.E, base.k, base.dtype) for _ in range(2)]
+    _, gen_s = upload_and_pack(base, args.seed, paths[0], torch, synth, keep=False)
+    paths[1].packed = paths[0].packed
+    x, logits = make_inputs(base, args.seed, synth)
+    x_d, l_d = dev(x, torch), dev(logits, torch)
+    rows = []
+    for m in ms:
+        c = replace(base, micro_batches=m, name=f"{base.name}_m{m}")
+        r = time_workload(c, paths, x_d, l_d, args.steps, args.warmup, torch, R, synth, breakdown=False)
+        rows.append({"m": m, "tokens_per_expert_mean": round(c.T * c.k / c.E / m, 1),
+                     "two_stream_ms_per_step": round(r["ms_per_step"], 5),
+                     "one_stream_ms_per_step": round(r["serial_ms"], 5) if r["serial_ms"] is not None else None,
+                     "tokens_per_s": round(c.T / (r["ms_per_step"] * 1e-3), 1),
+                     "ffn_input_avg_launch_ms": round(r["ffn_in_ms"], 5)})
+    for p in paths:
+        p.close()
+    del paths, x_d, l_d
+    torch.cuda.empty_cache()
+    return {"workload": base.name, "T": base.T, "d": base.d, "f": base.f, "E": base.E, "k": base.k,
+            "streams": 2, "steps": args.steps, "warmup": args.warmup, "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="mixtral_T256")
+    ap.add_argument("--workload", default=None,
+                    help="time this workload only (default: mixtral_T256 as the headline, plus the Mixtral-shaped "
+                         "T sweep and the micro-batch study)")
     ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--sweep", action="store_true", help="also run the Mixtral-shaped T sweep (one line per T)")
+    ap.add_argument("--sweep", action="store_true", help="with --workload mixtral_*: also run the T sweep")
+    ap.add_argument("--sweep-lines", action="store_true", help="print one JSON line per sweep point as well")
+    ap.add_argument("--no-sweep", action="store_true", help="default run without the T sweep")
+    ap.add_argument("--no-micro-batch-study", action="store_true", help="default run without the micro-batch study")
     ap.add_argument("--micro-batches", type=int, default=0,
                     help="override the workload's micro-batch count m (m > 1: two alternating streams)")
     ap.add_argument("--fit", action="store_true",
-                    help="with --sweep: fit the paper's expert-time model T_e = k3*b_e + k4 to the measured FFN times")
+                    help="with the sweep: fit the paper's expert-time model T_e = k3*b_e + k4 to the measured FFN times")
     ap.add_argument("--expert-plan", default="", metavar="N,S",
                     help="also time every node's share of the expert FFN for N expert nodes, plain deployment "
                          "against the greedy plan with S slots per node (hot experts get copies)")
     ap.add_argument("--per-expert", action="store_true",
                     help="also time every expert's own rows alone (both FFN GEMMs) and print rows, time, rates and roof")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--vendor-gemm", action="store_true",
-                    help="also time the vendor GEMM library on the two expert GEMMs of this workload (one call per "
-                         "expert, distinct weights, uniform rows) and print it as an extra JSON line")
     ap.add_argument("--ceilings", action="store_true",
                     help="time the streaming-read and register-only MFMA probes even with --no-cpu-baseline")
     ap.add_argument("--cpu-sample-tokens", type=int, default=256)
@@ -467,19 +503,14 @@ def main():
                           "ms": round(dt * 1e3, 4), "GB/s_read_plus_write": round(2 * n / dt / 1e9, 1)}))
         return
 
-    if args.workload in synth.CONFIGS:
-        cfg = synth.CONFIGS[args.workload]
-    elif "_T" in args.workload and any(n.startswith(args.workload.split("_T")[0] + "_T") for n in synth.CONFIGS):
-        base, T = args.workload.split("_T")          # a named shape at another token count, e.g. mixtral_T1024
-        cfg = next(c for n, c in synth.CONFIGS.items() if n.startswith(base + "_T")).with_T(int(T))
-    else:
-        raise SystemExit(f"unknown workload {args.workload!r}; known: {sorted(synth.CONFIGS)}, or one of these shapes at another token count (<shape>_T<N>)")
-
+    full = args.workload is None          # the default run: headline + sweep + micro-batch study
+    cfg = resolve_workload(args.workload or "mixtral_T256", synth)
     if args.micro_batches > 0:
         from dataclasses import replace
         cfg = replace(cfg, micro_batches=args.micro_batches, name=f"{cfg.name}_m{args.micro_batches}")
-    sweep_T = list(synth.MIXTRAL_SWEEP_T) if args.sweep else []
-    T_max = max([cfg.T] + (sweep_T if cfg.name.startswith("mixtral") else []))
+    do_sweep = cfg.name.startswith("mixtral") and cfg.micro_batches == 1 and ((full and not args.no_sweep) or args.sweep)
+    sweep_T = list(synth.MIXTRAL_SWEEP_T) if do_sweep else []
+    T_max = max([cfg.T] + sweep_T)
     if cfg.micro_batches > 1:
         T_max = max(b - a for a, b in synth.microbatch_ranges(cfg.T, cfg.micro_batches))
     paths = [B.MoEPath(T_max, cfg.d, cfg.f, cfg.E, cfg.k, cfg.dtype) for _ in range(2 if cfg.micro_batches > 1 else 1)]
@@ -499,31 +530,38 @@ def main():
             cpu = cpu_baseline(c, args.seed, W, x, logits, moe_oracle, args.cpu_sample_tokens)
         return result_line(c, args.steps, args.warmup, r, R, cpu, measure_ceilings(paths[0], B, torch) if want_cpu or args.ceilings else None)
 
+    head = run(cfg, not args.no_cpu_baseline)
     lines = []
-    if args.sweep and cfg.name.startswith("mixtral"):
-        for T in sweep_T:
-            if T != cfg.T:
-                lines.append(run(cfg.with_T(T), False))
-                print(json.dumps(lines[-1]), flush=True)
-    lines.append(run(cfg, not args.no_cpu_baseline))
+    for T in sweep_T:
+        if T == cfg.T:
+            lines.append(head)
+            continue
+        print(f"[bench] sweep point T = {T} ...", file=sys.stderr, flush=True)
+        lines.append(run(cfg.with_T(T), False))
+        if args.sweep_lines:
+            print(json.dumps(lines[-1]), flush=True)
+    if lines:
+        head["sweep"] = [sweep_entry(l) for l in lines]
+        big = lines[-1]
+        head["roofline_large_batch"] = dict(big["roofline"], workload=big["config"]["workload"],
+                                            tokens_per_expert_mean=big["config"]["tokens_per_expert_mean"])
+        if head.get("ceilings", {}).get("mfma_loop_TFLOP/s") and big["roofline"]["bound"] == "mfma":
+            head["roofline_large_batch"]["frac_of_measured_ceiling"] = round(
+                big["roofline"]["achieved"] / head["ceilings"]["mfma_loop_TFLOP/s"], 4)
     if args.fit and len(lines) >= 4:
         # expert time of one layer call = the two FFN GEMMs; b_e = mean tokens per expert
         pts = sorted((l["config"]["tokens_per_expert_mean"],
                       l["layer"]["calls_ms"]["ffn_input"] + l["layer"]["calls_ms"]["ffn_output"]) for l in lines)
         fit = R.fit_expert_time([p[0] for p in pts], [p[1] for p in pts], split=128)
         fit["roofline_ridge_b"] = R.ridge_batch(R.MI355X_BF16_DENSE_FLOPS, R.MI355X_HBM_BYTES_PER_S)
-        print(json.dumps({"expert_time_model": "T_e[ms] = k3*b_e + k4", "points": pts, "fit": fit}), flush=True)
-    if args.vendor_gemm:
-        y = vendor_gemm_yardstick(cfg, torch)
-        y["this_library_ms"] = {n: lines[-1]["layer"]["calls_ms"][n] for n in ("ffn_input", "ffn_output")}
-        print(json.dumps(y), flush=True)
+        head["expert_time_model"] = {"model": "T_e[ms] = k3*b_e + k4", "points": pts, "fit": fit}
     if args.per_expert:
         x, logits = make_inputs(cfg, args.seed, synth)
         a0, b0 = synth.microbatch_ranges(cfg.T, cfg.micro_batches)[0]     # the first micro-batch stands for the others
         from dataclasses import replace as _replace
         pe = per_expert_breakdown(_replace(cfg, T=b0 - a0), paths[0], dev(x[a0:b0], torch), dev(logits[a0:b0], torch),
                                   B, R, torch)
-        pe["fused_launches_ms"] = round(lines[-1]["layer"]["calls_ms"]["ffn_input"] + lines[-1]["layer"]["calls_ms"]["ffn_output"], 4)
+        pe["fused_launches_ms"] = round(head["layer"]["calls_ms"]["ffn_input"] + head["layer"]["calls_ms"]["ffn_output"], 4)
         print(json.dumps(pe), flush=True)
     if args.expert_plan:
         N, S = (int(v) for v in args.expert_plan.split(","))
@@ -532,9 +570,15 @@ def main():
         x, logits = make_inputs(cfg, args.seed, synth)
         print(json.dumps(expert_plan_experiment(cfg, paths[0], dev(x, torch), dev(logits, torch), N, S, B, torch)),
               flush=True)
-    print(json.dumps(lines[-1]), flush=True)
     for p in paths:
         p.close()
+    del paths, W
+    torch.cuda.empty_cache()
+    if full and not args.no_micro_batch_study:
+        print("[bench] micro-batch study on finegrained_T8192 ...", file=sys.stderr, flush=True)
+        head["micro_batch_study"] = micro_batch_study(args, torch, B, R, synth)
+    head["library_source_hash"] = B.library_source_hash()
+    print(json.dumps(head), flush=True)
 
 
 if __name__ == "__main__":

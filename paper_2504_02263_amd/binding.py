@@ -88,6 +88,16 @@ def load_library() -> ctypes.CDLL:
     return lib
 
 
+def library_source_hash() -> str:
+    """Hash of the sources the loaded library was built from (as build.py recorded it)."""
+    load_library()
+    try:
+        with open(_build.STAMP_PATH) as fh:
+            return fh.read().strip()
+    except OSError:
+        return ""
+
+
 def _ptr(t) -> Optional[int]:
     """Device address of a tensor (or a raw int address, or None)."""
     if t is None:

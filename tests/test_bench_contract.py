@@ -48,3 +48,30 @@ def test_json_line_fields_on_the_small_layer():
     assert sum(j["config"]["tokens_per_expert"]) == j["config"]["T"] * j["config"]["k"]
     cpu = j["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0
+
+
+@pytest.mark.gpu
+def test_default_run_carries_the_whole_curve():
+    """No --workload: the headline workload plus the Mixtral-shaped sweep (both roofline regimes) and the
+    micro-batch study, still as ONE JSON line that honours --steps and --warmup."""
+    r = _run("--steps", "2", "--warmup", "1", "--cpu-sample-tokens", "16")
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [l for l in r.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    j = json.loads(lines[0])
+    assert j["config"]["workload"] == "mixtral_T256" and j["steps"] == 2 and j["warmup"] == 1
+    assert [e["T"] for e in j["sweep"]] == [32, 64, 128, 256, 512, 1024, 2048, 4096]
+    for e in j["sweep"]:
+        f = e["ffn_input"]
+        assert f["bound"] in ("hbm", "mfma") and abs(f["frac"] - f["achieved"] / f["peak"]) < 1e-3
+        assert abs(e["tokens_per_s"] - e["T"] / (e["ms_per_step"] * 1e-3)) <= 1e-3 * e["tokens_per_s"]
+    at256 = next(e for e in j["sweep"] if e["T"] == 256)
+    assert at256["ms_per_step"] == j["ms_per_step"] and at256["ffn_input"]["frac"] == j["roofline"]["frac"]
+    assert j["sweep"][0]["ffn_input"]["bound"] == "hbm" and j["sweep"][-1]["ffn_input"]["bound"] == "mfma"
+    big = j["roofline_large_batch"]
+    assert big["workload"] == "mixtral_T4096" and big["bound"] == "mfma" and big["unit"] == "TFLOP/s"
+    assert j["roofline"]["traffic"] is None or "profiles/" in j["roofline"]["traffic_source"]
+    mb = j["micro_batch_study"]
+    assert mb["workload"] == "finegrained_T8192" and [row["m"] for row in mb["rows"]] == [1, 2, 3, 4]
+    assert all(row["two_stream_ms_per_step"] > 0 for row in mb["rows"])
+    assert j["cpu_baseline"]["gflops"] > 0 and j["cpu_baseline"]["cores_source"]
