@@ -1,6 +1,6 @@
 """GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
 inputs. Integer outputs (indices, counts, offsets, permutations, copied rows) must be bit-exact;
-token weights within 1e-6; floating-point tensors within relative Frobenius error 1e-5 (fp32) or
+token weights within a few float32 roundings (w_tol below); floating-point tensors within relative Frobenius error 1e-5 (fp32) or
 1e-2 (bf16)."""
 import numpy as np
 import pytest
@@ -13,7 +13,15 @@ from workloads import synth
 pytestmark = pytest.mark.gpu
 
 TOL = {"f32": 1e-5, "bf16": 1e-2}
-W_TOL = 1e-6   # |w_gpu - w_oracle|: fp32 exp/div on weights <= 1 (a few ulp) vs the float64 oracle
+
+
+def w_tol(k: int) -> float:
+    """Bound on |w_gpu - w_oracle| for the softmax over k picks, float32 on the GPU against float64.
+    With u = 2^-24 (rounding to nearest) and weights <= 1: expf is within 1 ulp = 2u, in the numerator and
+    (as a weighted mean) in the denominator: 4u; the subtraction l_j - l_0 is rounded, which moves exp by
+    u*|x|e^-|x| <= 0.37u, twice: 0.74u; the k-term sum rounds k - 1 times: (k - 1)u; the division: u.
+    Together (4.74 + k)u, rounded up to (5 + k)u: 4.2e-7 at k = 2, 6.6e-7 at k = 6; never looser than 1e-6."""
+    return min(1e-6, (5 + k) * 2.0 ** -24)
 
 
 def dev(a: np.ndarray) -> torch.Tensor:
@@ -56,7 +64,7 @@ def check_integers(path, ref, T, k):
     assert (host(path.pos)[:T] == ref["pos"]).all()
     assert (host(path.src)[:A] == ref["src"]).all()
     assert (host(path.xp)[:A] == ref["xp"]).all()                 # rows are copied bit for bit
-    np.testing.assert_allclose(host(path.topk_w)[:T], ref["topk_w"], rtol=0, atol=W_TOL)
+    np.testing.assert_allclose(host(path.topk_w)[:T], ref["topk_w"], rtol=0, atol=w_tol(k))
 
 
 # ------------------------------------------------------------------------------- route
@@ -85,7 +93,7 @@ def test_route_bit_exact(T, E, k):
     assert (host(g_idx)[:T] == idx).all()
     assert (host(g_counts) == counts).all()
     assert (host(g_offsets) == offsets).all()
-    np.testing.assert_allclose(host(g_w)[:T], w, rtol=0, atol=W_TOL)
+    np.testing.assert_allclose(host(g_w)[:T], w, rtol=0, atol=w_tol(k))
     if T:
         np.testing.assert_allclose(host(g_w)[:T].sum(1), 1.0, rtol=0, atol=4e-7)
 
@@ -297,7 +305,7 @@ def test_gate_route(T, d, E, k, dtype):
     idx, w, counts, offsets = O.route(g_logits, k)
     assert (host(path.topk_idx)[:T] == idx).all()
     assert (host(path.counts) == counts).all() and (host(path.offsets) == offsets).all()
-    np.testing.assert_allclose(host(path.topk_w)[:T], w, rtol=0, atol=W_TOL)
+    np.testing.assert_allclose(host(path.topk_w)[:T], w, rtol=0, atol=w_tol(k))
     # without the logits output the routing is the same
     first = host(path.topk_idx).copy()
     path.gate_route(dev(x), dev(w_r), None)
@@ -320,7 +328,7 @@ def test_route_largest_supported_k_and_E():
     torch.cuda.synchronize()
     assert (host(path.topk_idx) == idx).all() and (host(path.counts) == counts).all()
     assert (host(path.offsets) == offsets).all()
-    np.testing.assert_allclose(host(path.topk_w), w, rtol=0, atol=W_TOL)
+    np.testing.assert_allclose(host(path.topk_w), w, rtol=0, atol=w_tol(k))
     path.close()
 
 
