@@ -358,6 +358,11 @@ def per_call_rates(cfg, r, R):
     return out
 
 
+def synth_skew(cfg):
+    from workloads import synth
+    return synth.expected_load_skew(cfg)
+
+
 def result_line(cfg, steps, warmup, r, R, cpu, ceilings=None):
     ms_per_step, counts, cost = r["ms_per_step"], r["counts"], r["cost"]
     sec = ms_per_step * 1e-3
@@ -368,7 +373,7 @@ def result_line(cfg, steps, warmup, r, R, cpu, ceilings=None):
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "f": cfg.f, "E": cfg.E, "k": cfg.k,
-                   "micro_batches": cfg.micro_batches,
+                   "micro_batches": cfg.micro_batches, "load_skew_hint": round(synth_skew(cfg), 3),
                    "tokens_per_expert_mean": cfg.T * cfg.k / cfg.E / cfg.micro_batches,
                    "tokens_per_expert_max": int(counts.max()), "tokens_per_expert_min": int(counts.min()),
                    "tokens_per_expert": [int(c) for c in counts]},
@@ -513,7 +518,11 @@ def main():
     T_max = max([cfg.T] + sweep_T)
     if cfg.micro_batches > 1:
         T_max = max(b - a for a, b in synth.microbatch_ranges(cfg.T, cfg.micro_batches))
-    paths = [B.MoEPath(T_max, cfg.d, cfg.f, cfg.E, cfg.k, cfg.dtype) for _ in range(2 if cfg.micro_batches > 1 else 1)]
+    # the one thing a serving engine knows about the load that the kernels cannot see from the host: how skewed
+    # the router is (1 for the near-uniform workloads; the Zipf workload states its own skew)
+    skew = synth.expected_load_skew(cfg)
+    paths = [B.MoEPath(T_max, cfg.d, cfg.f, cfg.E, cfg.k, cfg.dtype, load_skew=skew)
+             for _ in range(2 if cfg.micro_batches > 1 else 1)]
     W, gen_s = upload_and_pack(cfg, args.seed, paths[0], torch, synth)
     for p in paths[1:]:
         p.packed = paths[0].packed          # one packed weight set serves every stream

@@ -50,12 +50,17 @@ typedef enum {
 typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
 
 typedef struct {
-  int32_t T_max; /* largest T any call will be given */
+  int32_t T_max; /* largest T any call will be given; T_max * k <= 2^22 */
   int32_t d;     /* hidden size; multiple of 128 */
   int32_t f;     /* expert intermediate size; multiple of 128 */
   int32_t E;     /* experts, 1..256 */
   int32_t k;     /* experts per token, 1..min(E, 64) */
   int32_t dtype; /* moe_dtype */
+  /* Optional hint, 0 = unknown (treated as 1): how many times the mean number of rows the most popular
+   * experts are expected to get (a serving engine that tracks expert popularity, as the paper's load
+   * balancer does, Section 6 "Load balance", knows this; per-batch counts never leave the device). It only
+   * helps pick the GEMM kernel for a launch; results never depend on it. Must be 0 or a finite value >= 1. */
+  float load_skew;
 } moe_config;
 
 /* Validate cfg and build a context (host memory only). MOE_ERR_INVALID_ARG for a null
@@ -105,8 +110,8 @@ moe_status moe_gate_route(moe_ctx* ctx, int32_t T, const void* x, const float* w
                           int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* offsets, void* stream);
 
 /*
- * Dispatch pack (Section 2.2 "send input tokens to the experts"; Section 6 "scatter tokens to
- * respective experts"): stable counting sort of the A assignments by expert.
+ * Dispatch pack (Section 2.2: each token goes to the experts its routing picked; Section 6 "Fused
+ * kernels": the scatter step): stable counting sort of the A assignments by expert.
  * In: x[T, d], topk_idx[T, k], offsets[E + 1] (as written by moe_route).
  * Out: xp[A, d]   expert-contiguous copy of the tokens: rows offsets[e]..offsets[e+1]-1 belong
  *                 to expert e, in ascending flat assignment order t*k + j
@@ -176,7 +181,7 @@ moe_status moe_ffn_output(moe_ctx* ctx, int32_t T, const void* h, const int32_t*
  * for S expert copies (N*S >= M), so that the largest node cost
  *     C_j = sum_i x[i][j] * max(a[i], K)        (x[i][j] = fraction of expert i served by node j)
  * is small: a[i] = cost of computing expert i's active tokens over the last period, K = lowest
- * cost a cold expert can have. The paper names a greedy approximation without detail; the steps
+ * cost a cold expert can have. The paper solves this greedily and gives no steps (Section 6 "Load balance"); the steps
  * taken are: (1) while spare slots remain, the expert with the largest per-copy share
  * max(a[i], K) / replicas[i] gets one more copy (at most one per node), unless that share is already
  * no more than the mean node cost; (2) the copies of an expert split it equally (x = 1 / replicas[i]);

@@ -85,8 +85,8 @@ def route(logits: np.ndarray, k: int):
 
 
 def dispatch(x: np.ndarray, topk_idx: np.ndarray, offsets: np.ndarray):
-    """Scatter tokens into an expert-contiguous buffer (Section 2.2 "send input tokens to the
-    experts"; Section 6 "scatter tokens to respective experts").
+    """Put every token's row into an expert-contiguous buffer, once per expert it was routed to
+    (Section 2.2: tokens go to their experts; Section 6 "Fused kernels": the scatter step).
 
     Assignments are visited in flat order i = t*k + j; each takes the next free row of
     its expert's segment [offsets[e], offsets[e+1]).

@@ -9,7 +9,7 @@ fraction of expert i served by node j (each expert's fractions sum to one), a_i
 the cost of computing expert i's active tokens and K the lowest cost a cold
 expert can have, the plan should minimise the largest node cost
     C_j = sum_i x[i][j] * max(a_i, K).
-The paper solves this with "a greedy approximation" and gives no further detail,
+The paper solves this greedily and gives no further detail,
 so the steps below are a reading, taken in this order:
 
   0. w_i = max(a_i, K).

@@ -30,7 +30,8 @@ EXPORTS = ("moe_create", "moe_destroy", "moe_last_error", "moe_status_string", "
 
 class MoeConfig(ctypes.Structure):
     _fields_ = [("T_max", ctypes.c_int32), ("d", ctypes.c_int32), ("f", ctypes.c_int32),
-                ("E", ctypes.c_int32), ("k", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+                ("E", ctypes.c_int32), ("k", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("load_skew", ctypes.c_float)]
 
 
 class MoeError(RuntimeError):
@@ -122,9 +123,9 @@ def _check(ctx, status: int):
         raise MoeError(status, f"{lib.moe_status_string(status).decode()} {msg}".strip())
 
 
-def moe_create(T_max: int, d: int, f: int, E: int, k: int, dtype: str) -> int:
+def moe_create(T_max: int, d: int, f: int, E: int, k: int, dtype: str, load_skew: float = 0.0) -> int:
     lib = load_library()
-    cfg = MoeConfig(T_max, d, f, E, k, _DTYPES[dtype][0])
+    cfg = MoeConfig(T_max, d, f, E, k, _DTYPES[dtype][0], load_skew)
     ctx = ctypes.c_void_p()
     status = lib.moe_create(ctypes.byref(cfg), ctypes.byref(ctx))
     if status != MOE_OK:
@@ -253,13 +254,13 @@ class NodeShare:
 class MoEPath:
     """Buffers for one (T_max, d, f, E, k, dtype) layer plus the four hot calls over them."""
 
-    def __init__(self, T_max: int, d: int, f: int, E: int, k: int, dtype: str, device="cuda:0"):
+    def __init__(self, T_max: int, d: int, f: int, E: int, k: int, dtype: str, device="cuda:0", load_skew: float = 0.0):
         if not torch.cuda.is_available():
             raise RuntimeError("MoEPath needs a GPU: there is no CPU path")
         self.T_max, self.d, self.f, self.E, self.k, self.dtype = T_max, d, f, E, k, dtype
         self.device = torch.device(device)
         self.tdtype = _DTYPES[dtype][1]
-        self.ctx = moe_create(T_max, d, f, E, k, dtype)
+        self.ctx = moe_create(T_max, d, f, E, k, dtype, load_skew)
         A = max(T_max * k, 1)
         dev, i32 = self.device, torch.int32
         self.topk_idx = torch.empty((max(T_max, 1), k), dtype=i32, device=dev)

@@ -13,7 +13,6 @@
 // segment e is expert e's rows, begin = offsets, end = offsets + 1; with several copies of a
 // popular expert (Section 6, "Load balance") a copy is a segment holding part of that expert's rows.
 #include <math.h>
-#include <stdlib.h>
 #include <type_traits>
 #include "moe_internal.h"
 
@@ -43,6 +42,8 @@ struct Segs {
   int experts;            // experts in the packed weights
   int rows_cap;           // rows the activation buffers hold; ranges are clipped to it
   int tall_first;         // large-batch kernel: order the segments by tile height (see locate_tile)
+  int rows_above;         // this launch takes only the segments with rows_above < rows <= rows_upto:
+  int rows_upto;          //   the counts stay on the device, so each kernel picks its own segments there
 };
 
 struct TileLoc {
@@ -77,7 +78,8 @@ __device__ __forceinline__ TileLoc locate_tile(const Segs& segs, int BM, int per
     lo = max(0, min(segs.begin[tid], segs.rows_cap));
     hi = max(lo, min(segs.end[tid], segs.rows_cap));
   }
-  const int rows = hi - lo;
+  int rows = hi - lo;
+  if (rows <= segs.rows_above || rows > segs.rows_upto) rows = 0;  // another launch's segment
   int nt = (rows + BM - 1) / BM;
   int step = nt == 0 ? 0 : BM;  // rows per tile
   if (BALANCED && nt > 0) {
@@ -200,13 +202,13 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint4* __restrict_
 // c + NST + 1 are issued in stage c. The token share for chunk c + 1 is written to LDS at the end
 // of stage c (double-buffered slab, one barrier per chunk). Loads never branch (indices past the
 // end are clamped; what they fetch is unused), which keeps the s_waitcnt vmcnt counts exact: about
-// NST - 1 chunks stay in flight across every wait. NTL marks the weight loads non-temporal (for
-// weights that are read once; worth +13 % of streaming bandwidth).
+// NST - 1 chunks stay in flight across every wait. Weights that are read once are loaded non-temporally
+// (worth +13 % of streaming bandwidth).
 //
 // LDS slab: [BM rows][8 units of 16 B], unit index XOR ((row >> 1) & 7): both the row-major
 // writes and the operand-order reads (32 rows, same logical unit) are free of bank conflicts
 // (measured with the LDS bank-conflict counter; XOR with row & 7 is not).
-template <int MTW, int NW, int NST, int WN, int WM, bool GATEUP, bool NTL>
+template <int MTW, int NW, int NST, int WN, int WM, bool GATEUP>
 struct Gemm {
   static constexpr int THREADS = 64 * WN * WM;
   static constexpr int BM = 32 * MTW * WM;
@@ -218,8 +220,9 @@ struct Gemm {
   const u32x4* xrow[PASSES];
   int NC, swz_w, trow, frow, fg, mbase;
 
-  // MU = 32-row groups of this wavefront that hold real rows (the others are skipped entirely)
-  template <int MU>
+  // MU = 32-row groups of this wavefront that hold real rows (the others are skipped entirely);
+  // NTL: non-temporal weight loads (weights that no other tile reads).
+  template <int MU, bool NTL>
   __device__ __forceinline__ void run(floatx16 (&acc)[NW][MTW]) {
     u32x4 wreg[NST][4 * NW];
     u32x4 treg[NST][PASSES];
@@ -289,14 +292,14 @@ struct Gemm {
   }
 };
 
-template <int MTW, int NW, int NST, int WN, int WM, bool GATEUP, bool NTL>
+template <int MTW, int NW, int NST, int WN, int WM, bool GATEUP>
 __global__ __launch_bounds__(64 * WN * WM) void ffn_bf16_kernel(const u32x4* __restrict__ X, const Segs segs,
                                                                const u32x4* __restrict__ Wp, __bf16* __restrict__ C,
                                                                int N, int K) {
   static_assert(NST % 2 == 0, "chunk parity must equal ring-slot parity");
   static_assert(WN * WM >= 4, "the tile locator needs one thread per expert (256)");
   static_assert(NW == 2 || !GATEUP, "gate and up fragments are consumed together");
-  using G = Gemm<MTW, NW, NST, WN, WM, GATEUP, NTL>;
+  using G = Gemm<MTW, NW, NST, WN, WM, GATEUP>;
   constexpr int BM = G::BM;
   __shared__ u32x4 slab[2][BM * 8];
 
@@ -348,8 +351,15 @@ __global__ __launch_bounds__(64 * WN * WM) void ffn_bf16_kernel(const u32x4* __r
   // stages and barriers whatever its count is.
   int mu = (rows - g.mbase * 32 + 31) / 32;
   mu = __builtin_amdgcn_readfirstlane(max(0, min(mu, MTW)));
+  // A segment of up to BM rows is one tile and its weights are read once: non-temporal loads (worth
+  // +13 % of streaming bandwidth). The tiles of a taller segment sit next to each other in the queue
+  // and read the same weights: cached loads, so that the second tile finds them in L2.
+  const bool once = loc.tiles == 1;
   static_for<0, MTW + 1>([&](auto mu_) {
-    if (mu == decltype(mu_)::value) g.template run<decltype(mu_)::value>(acc);
+    if (mu == decltype(mu_)::value) {
+      if (once || !GATEUP) g.template run<decltype(mu_)::value, true>(acc);
+      else g.template run<decltype(mu_)::value, false>(acc);
+    }
   });
 
   if (!has_n) return;
@@ -650,13 +660,13 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ 
   __shared__ float xs[BM][BK + 1];
   __shared__ float ws[NW][BN][BK + 1];
 
-  const TileLoc loc = locate_tile<false>(segs, BM, 1, blockIdx.y);
+  const TileLoc loc = locate_tile<false>(segs, BM, 1, blockIdx.x);  // m-tiles on grid.x: no 65535 limit
   if (loc.expert < 0) return;
   const int wexp = segment_expert(segs, loc.expert);
   if (wexp < 0) return;
   const int tid = threadIdx.x, tx = tid & 63, ty = tid >> 6;
   const int rows = loc.rows;
-  const int n0 = blockIdx.x * BN;
+  const int n0 = blockIdx.y * BN;
 
   float acc[NW][8];
 #pragma unroll
@@ -714,33 +724,29 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ 
 // the balanced split of the large-batch kernel may take one more tile per segment.
 inline int max_m_tiles(int A, int S, int BM, int extra = 0) { return A / BM + (1 + extra) * (S < A ? S : A); }
 
-template <int MTW, int NW, int NST, int WN, int WM, bool GATEUP, bool NTL>
-void launch_bf16(const void* X, const Segs& segs, const void* Wp, void* C, int A, int N, int K, hipStream_t stream) {
-  constexpr int BM = 32 * MTW * WM;
+// `tiles` = upper bound on the m-tiles of the segments this launch takes (sizes the grid).
+template <int MTW, int NW, int NST, int WN, int WM, bool GATEUP>
+void launch_bf16(const void* X, const Segs& segs, const void* Wp, void* C, int tiles, int N, int K, hipStream_t stream) {
   const int NP = GATEUP ? N / 32 : N / 64;
   const int units = NW == 2 ? NP : 2 * NP;
   const int groups = (units + WN - 1) / WN;
   const int groups_per_xcd = (groups + 7) / 8;
-  const dim3 grid(8 * groups_per_xcd * max_m_tiles(A, segs.count, BM)), block(64 * WN * WM);
-  hipLaunchKernelGGL((ffn_bf16_kernel<MTW, NW, NST, WN, WM, GATEUP, NTL>), grid, block, 0, stream,
+  const dim3 grid(8 * groups_per_xcd * tiles), block(64 * WN * WM);
+  hipLaunchKernelGGL((ffn_bf16_kernel<MTW, NW, NST, WN, WM, GATEUP>), grid, block, 0, stream,
                      static_cast<const u32x4*>(X), segs, static_cast<const u32x4*>(Wp), static_cast<__bf16*>(C), N, K);
 }
 
+// rows_expected = rows the launch is expected to process (only orders the tile queue).
 template <bool GATEUP>
-void launch_bf16_wide(const void* X, Segs segs, const void* Wp, void* C, int A, int rows_hint, int N, int K,
-                      hipStream_t stream) {
+void launch_bf16_wide(const void* X, Segs segs, const void* Wp, void* C, int tiles, int rows_expected, int segs_expected,
+                      int N, int K, hipStream_t stream) {
   const int NP = GATEUP ? N / 32 : N / 64;
   const int groups_per_xcd = ((NP + 3) / 4 + 7) / 8;
   // Expected workgroups with a tile: about rows / 256 + half a tile per segment, times the column
   // groups. Up to four rounds of 256 compute units the tail decides the time: tall tiles first.
-  const float est = ((float)rows_hint / kWideBM + 0.5f * segs.count) * ((NP + 3) / 4);
-  // Tuning knob (read once): MOE_FFN_TALL_FIRST=0 / 1 forces index order / tall tiles first.
-  static const int forced = [] {
-    const char* v = getenv("MOE_FFN_TALL_FIRST");
-    return v ? atoi(v) : -1;
-  }();
-  segs.tall_first = forced >= 0 ? forced : est <= 4.f * 256.f;
-  const dim3 grid(8 * groups_per_xcd * max_m_tiles(A, segs.count, kWideBM, 1)), block(256);
+  const float est = ((float)rows_expected / kWideBM + 0.5f * segs_expected) * ((NP + 3) / 4);
+  segs.tall_first = est <= 4.f * 256.f;
+  const dim3 grid(8 * groups_per_xcd * tiles), block(256);
   hipLaunchKernelGGL((ffn_bf16_wide_kernel<GATEUP>), grid, block, 0, stream, static_cast<const u32x4*>(X), segs,
                      static_cast<const u32x4*>(Wp), static_cast<__bf16*>(C), N, K);
 }
@@ -802,51 +808,46 @@ hipError_t launch_slot_segments(const int32_t* slot_expert, const int32_t* slot_
 
 hipError_t launch_ffn_segments(const moe_config& cfg, int stage, const int32_t* seg_begin, const int32_t* seg_end,
                                const int32_t* seg_expert, int n_segs, int rows_bound, int rows_hint, int rows_cap,
-                               const void* in, const void* packed, void* out, hipStream_t stream) {
+                               int seg_rows_max, const void* in, const void* packed, void* out, hipStream_t stream) {
   const int A = rows_bound;
   if (A == 0 || n_segs == 0) return hipSuccess;
-  Segs segs{seg_begin, seg_end, seg_expert, n_segs, cfg.E, rows_cap, 0};
+  constexpr int kAll = 0x7fffffff;
+  Segs segs{seg_begin, seg_end, seg_expert, n_segs, cfg.E, rows_cap, 0, 0, kAll};
   const size_t one = (size_t)cfg.E * cfg.d * cfg.f;  // elements of one matrix set
   const int N = stage == 0 ? cfg.f : cfg.d, K = stage == 0 ? cfg.d : cfg.f;
   if (cfg.dtype == MOE_BF16) {
-    // The host never sees the per-segment row counts, so the kernel comes from the mean rows per
-    // segment. Up to mean + 2 sigma <= 128 (sigma = sqrt(mean), the spread of a near-uniform router):
-    // the streaming kernel, 8 wavefronts side by side along N, weights read once (non-temporal). Its
-    // tiles are always 128 rows tall: a wavefront only computes the 32-row groups that hold real rows,
-    // so at 8 rows per expert the tall tile costs nothing (measured: +-0.5 % against 32- or 64-row
-    // tiles), while under a skewed router the popular experts still fit one tile and their weights
-    // are read once (a Zipf load of 2...54 rows per expert: 15 % faster than with 32-row tiles). A few
-    // experts may need a second, short tile, which costs less than leaving the streaming kernel
-    // (measured at 104 and 112 mean rows: 3 % faster; at 120 mean rows the large-batch kernel wins).
-    // Above: the 256-row matrix-core-bound kernel, weights shared through L2; it needs K >= 256.
-    // Tuning knob (read once): MOE_FFN_LOAD_SKEW=<ratio> tells the choice how many times the mean the
-    // popular segments hold (a serving engine knows that from recent traffic; default 1 = uniform).
-    static const float skew = [] {
-      const char* v = getenv("MOE_FFN_LOAD_SKEW");
-      const float r = v ? (float)atof(v) : 1.f;
-      return r >= 1.f ? r : 1.f;
-    }();
-    const float mean = skew * (float)rows_hint / n_segs;
-    const float want = mean + 3.f * sqrtf(mean);
-    const bool stream128 = mean + 2.f * sqrtf(mean) <= 128.f;
-    // Tuning knob (read once): MOE_FFN_WIDE_ABOVE=<rows> moves the switch-over between the two kernels.
-    static const float wide_above = [] {
-      const char* v = getenv("MOE_FFN_WIDE_ABOVE");
-      return v ? (float)atof(v) : 128.f;
-    }();
-    const bool streaming = stream128 || want <= wide_above || K < 256;
+    // Two kernels; everything that depends on a segment's row count is decided where the counts are, on
+    // the device (tiles per segment, the 32-row groups a tile computes, cached or streaming weight loads,
+    // ring depths). The host only picks the kernel for the launch, from what it knows: the shape and the
+    // expected rows per segment.
+    //  - Streaming kernel: 8 wavefronts side by side along N, 128-row tiles. A wavefront only computes the
+    //    32-row groups that hold real rows, so at 8 rows per segment the tall tile costs nothing. A segment
+    //    of up to 128 rows is one tile whose weights are read once; a taller one (a skewed router's popular
+    //    expert) becomes several tiles that sit side by side in the queue and share the weights through L2.
+    //  - Large-batch kernel: 256-row tiles, one wavefront per SIMD, tiles of every height (1..8 row groups);
+    //    it needs K >= 256.
+    // The streaming kernel runs when a popular segment is expected to stay within one of its tiles:
+    // mean + 2 sigma <= 128 rows (mean = rows per segment x the caller's load_skew hint, sigma = sqrt(mean),
+    // the spread of a near-uniform router), or when no segment can be taller (seg_rows_max: an expert gets
+    // at most one row per token). Measured: at 104 and 112 mean rows it is
+    // 3 % faster, at 120 mean rows the large-batch kernel wins by 9 %.
+    constexpr int kStreamRows = 128;
+    const float mean = (cfg.load_skew >= 1.f ? cfg.load_skew : 1.f) * (float)rows_hint / n_segs;  // of a popular segment
+    const bool streaming = K < 256 || seg_rows_max <= kStreamRows || mean + 2.f * sqrtf(mean) <= (float)kStreamRows;
     const char* w = static_cast<const char*>(packed) + (stage == 0 ? 0 : 2 * one * 2);
-    if (stage == 0) {
-      if (streaming) launch_bf16<4, 2, 2, 8, 1, true, true>(in, segs, w, out, A, N, K, stream);
-      else launch_bf16_wide<true>(in, segs, w, out, A, rows_hint, N, K, stream);
+    if (streaming) {
+      const int tiles = max_m_tiles(A, n_segs, kStreamRows);
+      if (stage == 0) launch_bf16<4, 2, 2, 8, 1, true>(in, segs, w, out, tiles, N, K, stream);
+      else launch_bf16<4, 1, 2, 8, 1, false>(in, segs, w, out, tiles, N, K, stream);
     } else {
-      if (streaming) launch_bf16<4, 1, 2, 8, 1, false, true>(in, segs, w, out, A, N, K, stream);
-      else launch_bf16_wide<false>(in, segs, w, out, A, rows_hint, N, K, stream);
+      const int tiles = max_m_tiles(A, n_segs, kWideBM, 1);
+      if (stage == 0) launch_bf16_wide<true>(in, segs, w, out, tiles, rows_hint, n_segs, N, K, stream);
+      else launch_bf16_wide<false>(in, segs, w, out, tiles, rows_hint, n_segs, N, K, stream);
     }
     return hipGetLastError();
   }
   const float* wp = static_cast<const float*>(packed);
-  const dim3 grid((N + 63) / 64, max_m_tiles(A, n_segs, 32));
+  const dim3 grid(max_m_tiles(A, n_segs, 32), (N + 63) / 64);
   if (stage == 0)
     hipLaunchKernelGGL((ffn_f32_kernel<2>), grid, dim3(256), 0, stream, static_cast<const float*>(in), segs, wp,
                        wp + one, static_cast<float*>(out), N, K);
@@ -860,7 +861,8 @@ hipError_t launch_ffn_segments(const moe_config& cfg, int stage, const int32_t* 
 hipError_t launch_ffn_stage(const moe_config& cfg, int stage, int T, const void* in, const int32_t* offsets,
                             const void* packed, void* out, hipStream_t stream) {
   const int A = T * cfg.k;
-  return launch_ffn_segments(cfg, stage, offsets, offsets + 1, nullptr, cfg.E, A, A, A, in, packed, out, stream);
+  // an expert gets at most one row per token: no segment of the plain layer holds more than T rows
+  return launch_ffn_segments(cfg, stage, offsets, offsets + 1, nullptr, cfg.E, A, A, A, T, in, packed, out, stream);
 }
 
 }  // namespace moe

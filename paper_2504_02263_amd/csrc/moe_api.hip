@@ -57,10 +57,16 @@ moe_status check_config(const moe_config* c, const char** why) {
   }
   if (c->k > c->E) { *why = "k > E"; return MOE_ERR_INVALID_ARG; }
   if (c->dtype != MOE_F32 && c->dtype != MOE_BF16) { *why = "unknown dtype"; return MOE_ERR_INVALID_ARG; }
+  if (!(c->load_skew == 0.f || (c->load_skew >= 1.f && c->load_skew <= 1e6f))) {
+    *why = "load_skew must be 0 (unknown) or a finite value >= 1";
+    return MOE_ERR_INVALID_ARG;
+  }
   if (c->E > moe::kMaxExperts) { *why = "E > 256"; return MOE_ERR_UNSUPPORTED; }
   if (c->k > moe::kMaxTopK) { *why = "k > 64"; return MOE_ERR_UNSUPPORTED; }
   if (c->d % 128 || c->f % 128) { *why = "d and f must be multiples of 128"; return MOE_ERR_UNSUPPORTED; }
-  if ((int64_t)c->T_max * c->k > (int64_t)1 << 24) { *why = "T_max * k > 2^24"; return MOE_ERR_UNSUPPORTED; }
+  // Assignments per call. Counting (one workgroup) and ranking (at most 1024 workgroups, each recounting what
+  // lies before its share) are linear in T*k; beyond 4 M assignments a batch should be split by the caller.
+  if ((int64_t)c->T_max * c->k > (int64_t)1 << 22) { *why = "T_max * k > 2^22"; return MOE_ERR_UNSUPPORTED; }
   if ((int64_t)c->E * c->d * c->f > (int64_t)1 << 36) { *why = "E*d*f too large"; return MOE_ERR_UNSUPPORTED; }
   return MOE_OK;
 }
@@ -262,11 +268,11 @@ moe_status moe_expert_ffn_segments(moe_ctx* ctx, int32_t T, int32_t n_segs, int3
                 moe::kMaxExperts);
   const int A = T * ctx->cfg.k;
   const int hint = rows_hint > 0 ? (rows_hint < A ? rows_hint : A) : A;
-  hipError_t err = moe::launch_ffn_segments(ctx->cfg, 0, seg_begin, seg_end, seg_expert, n_segs, A, hint, A, xp,
+  hipError_t err = moe::launch_ffn_segments(ctx->cfg, 0, seg_begin, seg_end, seg_expert, n_segs, A, hint, A, A, xp,
                                             packed_w, h_ws, static_cast<hipStream_t>(stream));
   if (err == hipSuccess)
-    err = moe::launch_ffn_segments(ctx->cfg, 1, seg_begin, seg_end, seg_expert, n_segs, A, hint, A, h_ws, packed_w, y,
-                                   static_cast<hipStream_t>(stream));
+    err = moe::launch_ffn_segments(ctx->cfg, 1, seg_begin, seg_end, seg_expert, n_segs, A, hint, A, A, h_ws, packed_w,
+                                   y, static_cast<hipStream_t>(stream));
   return finish(ctx, "moe_expert_ffn_segments", err);
 }
 

@@ -35,10 +35,11 @@ hipError_t launch_ffn_stage(const moe_config& cfg, int stage, int T, const void*
                             const void* packed, void* out, hipStream_t stream);
 // The same two stages over explicit row segments: rows [seg_begin[s], seg_end[s]) use the weights of
 // expert seg_expert[s] (nullptr: expert s). rows_bound >= the rows of all segments together (sizes the
-// grid), rows_hint = their expected number (picks the tile shape), rows_cap = rows in `in` and `out`.
+// grid), rows_hint = their expected number, rows_cap = rows in `in` and `out`, seg_rows_max >= the rows of
+// the largest segment (a launch whose segments cannot exceed 128 rows needs one kernel only).
 hipError_t launch_ffn_segments(const moe_config& cfg, int stage, const int32_t* seg_begin, const int32_t* seg_end,
                                const int32_t* seg_expert, int n_segs, int rows_bound, int rows_hint, int rows_cap,
-                               const void* in, const void* packed, void* out, hipStream_t stream);
+                               int seg_rows_max, const void* in, const void* packed, void* out, hipStream_t stream);
 hipError_t launch_slot_segments(const int32_t* slot_expert, const int32_t* slot_copy, const int32_t* replicas,
                                 const int32_t* offsets, int n_slots, int E, int32_t* seg_begin, int32_t* seg_end,
                                 hipStream_t stream);

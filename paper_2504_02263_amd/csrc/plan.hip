@@ -3,7 +3,7 @@
 // Problem as the paper states it: spread M experts over N expert nodes, x[i][j] = fraction of
 // expert i served by node j (each expert's fractions sum to one), minimise the largest node cost
 // C_j = sum_i x[i][j] * max(a_i, K), a_i = cost of expert i's active tokens, K = lowest cost of a
-// cold expert. The paper names "a greedy approximation" and no more; the steps chosen here:
+// cold expert. The paper solves this greedily and names no steps; the steps chosen here:
 //   1. w_i = max(a_i, K). Every expert starts with one copy; while spare slots remain (a node has
 //      room for S copies), the expert with the largest per-copy share w_i / R_i (ties: lower index,
 //      fewer than N copies) gets one more copy, unless that share is already <= the mean node cost

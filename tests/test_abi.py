@@ -46,6 +46,11 @@ def test_create_validates_config():
         with pytest.raises(B.MoeError) as ei:
             B.moe_create(*bad)
         assert ei.value.status == status, bad
+    for skew in (0.5, -1.0, float("nan"), float("inf")):          # the load hint is 0 (unknown) or >= 1
+        with pytest.raises(B.MoeError) as ei:
+            B.moe_create(64, 256, 512, 8, 2, "bf16", load_skew=skew)
+        assert ei.value.status == B.MOE_ERR_INVALID_ARG, skew
+    B.moe_destroy(B.moe_create(64, 256, 512, 8, 2, "bf16", load_skew=3.5))
     lib = B.load_library()
     assert lib.moe_create(None, None) == B.MOE_ERR_INVALID_ARG
 

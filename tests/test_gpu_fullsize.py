@@ -54,10 +54,10 @@ def compare_outputs(name, got_out, x, idx, w, tokens, weights, counts):
 class Layer:
     """One weight set on the GPU (packed once) plus the host copy the oracle reads."""
 
-    def __init__(self, cfg, T_max, seed=0, paths=1):
+    def __init__(self, cfg, T_max, seed=0, paths=1, load_skew=0.0):
         self.cfg, self.seed = cfg, seed
         self.W = synth.make_all_expert_weights(cfg, seed, workers=16)
-        self.paths = [B.MoEPath(T_max, cfg.d, cfg.f, cfg.E, cfg.k, cfg.dtype) for _ in range(paths)]
+        self.paths = [B.MoEPath(T_max, cfg.d, cfg.f, cfg.E, cfg.k, cfg.dtype, load_skew=load_skew) for _ in range(paths)]
         self.path = self.paths[0]
         wg, wu, wd = (dev(w) for w in self.W)
         self.path.pack_weights(wg, wu, wd)
@@ -161,12 +161,14 @@ def test_dbrx_zipf_stratified():
     layer.close()
 
 
-@pytest.mark.parametrize("T", [256, 512])
-def test_dbrx_zipf_mixed_tile_classes(T):
+@pytest.mark.parametrize("T,hint", [(256, False), (256, True), (512, True)])
+def test_dbrx_zipf_mixed_tile_classes(T, hint):
     """Under the Zipf router at these batch sizes some experts hold a handful of rows and others hundreds:
-    one launch mixes decode-sized and large segments."""
+    one launch mixes decode-sized and large segments. Without the load_skew hint the mean (64 rows at
+    T = 256) sends the launch to the streaming kernel, whose popular experts become two tiles; with the
+    hint bench.py gives (the workload's own skew) the large-batch kernel runs every segment."""
     cfg = synth.CONFIGS["dbrx_zipf_T1024"].with_T(T)
-    layer = Layer(cfg, T_max=cfg.T)
+    layer = Layer(cfg, T_max=cfg.T, load_skew=synth.expected_load_skew(cfg) if hint else 0.0)
     counts = layer.check(cfg)
     assert counts.min() < 64 < 128 < counts.max()
     layer.close()

@@ -369,8 +369,8 @@ def test_expert_ffn_equals_its_two_stages_and_is_deterministic():
 
 @pytest.mark.parametrize("T,d,f,E,k", [(1500, 256, 384, 4, 2), (3000, 512, 256, 6, 3), (900, 384, 1024, 3, 1)])
 def test_both_gemm_kernels_give_the_same_bits(T, d, f, E, k):
-    """Which GEMM kernel runs is a host-side guess from the mean rows per segment (and environment knobs). Both
-    accumulate K in the same order with the same matrix-core instruction, so the guess must never show in a
+    """Which GEMM kernel a launch runs is picked on the host from the expected rows per segment. Both
+    accumulate K in the same order with the same matrix-core instruction, so the pick must never show in a
     result: the same rows through the streaming kernel (small rows hint) and the large-batch kernel (true hint)."""
     cfg = small_cfg(T, d, f, E, k, "bf16")
     x, logits = synth.make_activations(cfg, 3), synth.make_logits(cfg, 3)
@@ -550,3 +550,23 @@ def test_seeded_random_large_batch_layers(T, d, f, E, k, skew):
     err = rel_fro(host(path.out)[:T], ref["out"])
     assert err <= TOL["bf16"], (cfg.name, err)
     path.close()
+
+
+def test_millions_of_assignments():
+    """Near the largest batch a context accepts (T*k <= 2^22): 2.24 M assignments. The ranking kernel gives each
+    workgroup several 256-assignment chunks, the float32 GEMM's grid has more than 65 535 m-tiles, counting is
+    one workgroup; every integer is still exact and the layer output still matches the oracle."""
+    T, d, f, E, k = 280_000, 128, 128, 16, 8
+    cfg = small_cfg(T, d, f, E, k, "f32")
+    x = synth.make_activations(cfg, 12)
+    logits = synth.make_logits(cfg, 12)
+    W = synth.make_all_expert_weights(cfg, 12, workers=4)
+    ref = O.moe_layer(x, logits, k, lambda e: (W[0][e], W[1][e], W[2][e]))
+    path = run_layer(cfg, x, logits, W)
+    check_integers(path, ref, T, k)
+    err = rel_fro(host(path.out)[:T], ref["out"])
+    print(f"{cfg.name}: rel-Frobenius out {err:.2e}")
+    assert err <= TOL["f32"]
+    path.close()
+    with pytest.raises(B.MoeError):
+        B.moe_create((1 << 22) // k + 1, d, f, E, k, "f32")          # one token more than the limit

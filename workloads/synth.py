@@ -129,6 +129,17 @@ def zipf_bias(cfg: LayerConfig, seed: int = 0) -> np.ndarray:
     return (-cfg.zipf_s * np.log(rank.astype(np.float64))).astype(np.float32)
 
 
+def expected_load_skew(cfg: LayerConfig) -> float:
+    """How many times the mean load this workload's router is expected to give its most popular expert
+    (what a serving engine that tracks expert popularity would know): 1 for the near-uniform routers; under
+    the Zipf(s) bias, the head's share of first picks times E, capped at E / k because a token picks an
+    expert at most once."""
+    if cfg.zipf_s == 0.0:
+        return 1.0
+    p = np.arange(1, cfg.E + 1, dtype=np.float64) ** -cfg.zipf_s
+    return float(min(cfg.E * p[0] / p.sum(), cfg.E / cfg.k))
+
+
 def make_logits(cfg: LayerConfig, seed: int = 0) -> np.ndarray:
     """Router logits[T, E] float32 ~ N(0,1) (+ Zipf bias), for layers whose router input is the logits."""
     lg = _normal(_rng(seed, _TAG_LOGITS, cfg.T), (cfg.T, cfg.E), 1.0)
