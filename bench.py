@@ -65,13 +65,14 @@ def make_inputs(cfg, seed, synth):
 kSettleSeconds = 0.3
 
 
-def time_workload(cfg, paths, x_d, logits_d, steps, warmup, torch, R, synth, breakdown=True):
+def time_workload(cfg, paths, x_d, logits_d, steps, warmup, torch, R, synth, breakdown=True, w_router_d=None):
     """W warm-up steps, then exactly K timed steps between device synchronisations.
 
     A step runs the whole path over the batch. With cfg.micro_batches = m > 1 the batch is cut
     into m contiguous micro-batches issued on two alternating streams (each stream has its own
     buffer set; the packed weights are shared), the single-GPU echo of the paper's ping-pong
-    micro-batching (Section 4.1)."""
+    micro-batching (Section 4.1). With w_router_d the step starts at the gating GEMM (moe_gate_route_dispatch on
+    x and the gating matrix) instead of at given logits."""
     ranges = synth.microbatch_ranges(cfg.T, cfg.micro_batches)
     if cfg.micro_batches > 1:
         streams = [torch.cuda.Stream(), torch.cuda.Stream()]
@@ -83,7 +84,10 @@ def time_workload(cfg, paths, x_d, logits_d, steps, warmup, torch, R, synth, bre
             j = 0 if serial else i % len(streams)
             path, stream = paths[j], streams[j]
             T = b - a
-            path.route_dispatch(x_d[a:b], logits_d[a:b], T, stream)   # = moe_route then moe_dispatch
+            if w_router_d is not None:
+                path.gate_route_dispatch(x_d[a:b], w_router_d, None, T, stream)   # gating GEMM + routing + dispatch pack
+            else:
+                path.route_dispatch(x_d[a:b], logits_d[a:b], T, stream)   # = moe_route then moe_dispatch
             if ev is not None:
                 ev[i][0].record(stream)
             path.ffn_input(T, stream)
@@ -137,10 +141,15 @@ def time_workload(cfg, paths, x_d, logits_d, steps, warmup, torch, R, synth, bre
     calls = [lambda: path.route(logits_d[a:b], T, stream), lambda: path.dispatch(x_d[a:b], T, stream),
              lambda: path.route_dispatch(x_d[a:b], logits_d[a:b], T, stream),
              lambda: path.ffn_input(T, stream), lambda: path.ffn_output(T, stream), lambda: path.combine(T, stream)]
+    if w_router_d is not None:     # the gated forms come first, so that the FFN calls below see the gated routing
+        names = ["gate_route", "gate_route_dispatch"] + names[3:]
+        calls = [lambda: path.gate_route(x_d[a:b], w_router_d, None, T, stream),
+                 lambda: path.gate_route_dispatch(x_d[a:b], w_router_d, None, T, stream)] + calls[3:]
     reps = max(5, min(steps, 20)) if breakdown else 0
     acc = {n: [] for n in names}
     for _ in range(reps):
         evs = [torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)]
+        calls[-1]()                    # the first timed call must not pay for a device that just went idle
         evs[0].record(stream)
         for i, c in enumerate(calls):
             c()
@@ -347,7 +356,9 @@ def cpu_baseline(cfg, seed, W, x, logits, oracle_mod, sample_tokens):
 def per_call_rates(cfg, r, R):
     """Algorithmic GB/s (and TFLOP/s for the GEMMs) of every call of the first micro-batch, from the per-call times."""
     c, ms = r["cost"], r["calls_ms"]
+    gate = cfg.T // cfg.micro_batches * cfg.d * (2 if cfg.dtype == "bf16" else 4) + cfg.E * cfg.d * 4   # x and the gating matrix
     by = {"route": c.route_bytes, "dispatch": c.dispatch_bytes, "route_dispatch": c.route_bytes + c.dispatch_bytes,
+          "gate_route": gate + c.route_bytes, "gate_route_dispatch": gate + c.route_bytes + c.dispatch_bytes,
           "ffn_input": c.ffn_in_bytes, "ffn_output": c.ffn_out_bytes, "combine": c.combine_bytes}
     fl = {"ffn_input": c.ffn_in_flops, "ffn_output": c.ffn_out_flops}
     out = {}
@@ -363,7 +374,7 @@ def synth_skew(cfg):
     return synth.expected_load_skew(cfg)
 
 
-def result_line(cfg, steps, warmup, r, R, cpu, ceilings=None):
+def result_line(cfg, steps, warmup, r, R, cpu, ceilings=None, router="logits"):
     ms_per_step, counts, cost = r["ms_per_step"], r["counts"], r["cost"]
     sec = ms_per_step * 1e-3
     line = {
@@ -373,6 +384,8 @@ def result_line(cfg, steps, warmup, r, R, cpu, ceilings=None):
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "f": cfg.f, "E": cfg.E, "k": cfg.k,
+                   "router": "gating GEMM x*W_r inside the timed step (moe_gate_route_dispatch)" if router == "gate"
+                   else "logits given (moe_route_dispatch)",
                    "micro_batches": cfg.micro_batches, "load_skew_hint": round(synth_skew(cfg), 3),
                    "tokens_per_expert_mean": cfg.T * cfg.k / cfg.E / cfg.micro_batches,
                    "tokens_per_expert_max": int(counts.max()), "tokens_per_expert_min": int(counts.min()),
@@ -472,6 +485,9 @@ def main():
                          "against the greedy plan with S slots per node (hot experts get copies)")
     ap.add_argument("--per-expert", action="store_true",
                     help="also time every expert's own rows alone (both FFN GEMMs) and print rows, time, rates and roof")
+    ap.add_argument("--router", choices=("logits", "gate"), default="logits",
+                    help="logits: the step starts at given router logits, as the workloads define; gate: it starts at "
+                         "the gating GEMM on x and a seeded gating matrix (moe_gate_route_dispatch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ceilings", action="store_true",
                     help="time the streaming-read and register-only MFMA probes even with --no-cpu-baseline")
@@ -528,16 +544,22 @@ def main():
         p.packed = paths[0].packed          # one packed weight set serves every stream
     print(f"[bench] weights generated in {gen_s:.1f} s and packed", file=sys.stderr, flush=True)
 
+    w_router = synth.make_router_weight(cfg, args.seed) if args.router == "gate" else None
+    w_router_d = dev(w_router, torch) if w_router is not None else None
+
     def run(c, want_cpu):
         x, logits = make_inputs(c, args.seed, synth)
         x_d, l_d = dev(x, torch), dev(logits, torch)
-        r = time_workload(c, paths, x_d, l_d, args.steps, args.warmup, torch, R, synth)
+        r = time_workload(c, paths, x_d, l_d, args.steps, args.warmup, torch, R, synth, w_router_d=w_router_d)
         cpu = None
         if want_cpu:
             print("[bench] timing the CPU oracle on a sample ...", file=sys.stderr, flush=True)
             from oracle import moe_oracle  # the cpu_baseline leg is the only user of the oracle here
+            if w_router is not None:       # the oracle computes its own gate scores from the same gating matrix
+                logits = moe_oracle.gate_logits(x, w_router)
             cpu = cpu_baseline(c, args.seed, W, x, logits, moe_oracle, args.cpu_sample_tokens)
-        return result_line(c, args.steps, args.warmup, r, R, cpu, measure_ceilings(paths[0], B, torch) if want_cpu or args.ceilings else None)
+        return result_line(c, args.steps, args.warmup, r, R, cpu,
+                           measure_ceilings(paths[0], B, torch) if want_cpu or args.ceilings else None, router=args.router)
 
     head = run(cfg, not args.no_cpu_baseline)
     lines = []

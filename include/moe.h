@@ -135,6 +135,20 @@ moe_status moe_route_dispatch(moe_ctx* ctx, int32_t T, const float* logits, cons
                               void* stream);
 
 /*
+ * The whole step in front of the experts as one call, from the token embeddings to the packed rows:
+ * gating GEMM, top-k, normalised weights, per-expert counts and the scatter (Section 6 "Fused kernels" lists
+ * exactly these as one fused kernel). Arguments and outputs as moe_gate_route followed by moe_dispatch, bit
+ * for bit. Two launches for decode-sized batches (T <= 512 and T*k <= 2048): the gating kernel (GEMM + top-k
+ * + weights, one workgroup per block of tokens), then one kernel that counts, scans, ranks and copies the
+ * rows. A single launch would have every workgroup read all of x for the gating GEMM (there is no grid-wide
+ * barrier to share its result), which costs more than the second launch; the picks it hands over are
+ * T*k integers that stay in L2. Larger batches run the four kernels of the two calls.
+ */
+moe_status moe_gate_route_dispatch(moe_ctx* ctx, int32_t T, const void* x, const float* w_router, float* logits,
+                                   int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* offsets, void* xp,
+                                   int32_t* pos, int32_t* src, void* stream);
+
+/*
  * Expert FFN as a grouped SwiGLU GEMM (Section 4.2, Table 3; tensor-parallel degree 1):
  * for every expert e and row r in [offsets[e], offsets[e+1]):
  *     h[r, :] = silu(xp[r, :] * W_gate_e^T) .* (xp[r, :] * W_up_e^T)      ("FFN Input", fused)

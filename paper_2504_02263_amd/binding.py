@@ -25,7 +25,7 @@ _DTYPES = {"f32": (MOE_F32, torch.float32), "bf16": (MOE_BF16, torch.bfloat16)}
 EXPORTS = ("moe_create", "moe_destroy", "moe_last_error", "moe_status_string", "moe_packed_weight_bytes",
            "moe_pack_weights", "moe_route", "moe_gate_route", "moe_dispatch", "moe_expert_ffn", "moe_ffn_input", "moe_ffn_output",
            "moe_combine", "moe_plan_experts", "moe_slot_segments", "moe_expert_ffn_segments", "moe_route_dispatch",
-           "moe_expert_ffn_static", "moe_probe_stream_read", "moe_probe_mfma")
+           "moe_gate_route_dispatch", "moe_expert_ffn_static", "moe_probe_stream_read", "moe_probe_mfma")
 
 
 class MoeConfig(ctypes.Structure):
@@ -69,6 +69,8 @@ def load_library() -> ctypes.CDLL:
     lib.moe_gate_route.argtypes = [vp, i32] + [vp] * 7 + [vp]
     lib.moe_dispatch.argtypes = [vp, i32] + [vp] * 6 + [vp]
     lib.moe_route_dispatch.argtypes = [vp, i32] + [vp] * 9 + [vp]
+    lib.moe_gate_route_dispatch.argtypes = [vp, i32] + [vp] * 10 + [vp]
+    lib.moe_gate_route_dispatch.restype = ctypes.c_int
     lib.moe_expert_ffn.argtypes = [vp, i32] + [vp] * 5 + [vp]
     lib.moe_expert_ffn_static.argtypes = [vp, i32] + [vp] * 4 + [vp]
     lib.moe_expert_ffn_static.restype = ctypes.c_int
@@ -166,6 +168,13 @@ def moe_route_dispatch(ctx, T, logits, x, topk_idx, topk_w, counts, offsets, xp,
     _check(ctx, load_library().moe_route_dispatch(ctx, T, _ptr(logits), _ptr(x), _ptr(topk_idx), _ptr(topk_w),
                                                   _ptr(counts), _ptr(offsets), _ptr(xp), _ptr(pos), _ptr(src),
                                                   _stream(stream)))
+
+
+def moe_gate_route_dispatch(ctx, T, x, w_router, logits, topk_idx, topk_w, counts, offsets, xp, pos, src,
+                            stream=None) -> None:
+    _check(ctx, load_library().moe_gate_route_dispatch(ctx, T, _ptr(x), _ptr(w_router), _ptr(logits), _ptr(topk_idx),
+                                                       _ptr(topk_w), _ptr(counts), _ptr(offsets), _ptr(xp), _ptr(pos),
+                                                       _ptr(src), _stream(stream)))
 
 
 def moe_expert_ffn(ctx, T, xp, offsets, packed_w, h_ws, y, stream=None) -> None:
@@ -310,6 +319,11 @@ class MoEPath:
         moe_route_dispatch(self.ctx, T, logits, x, self.topk_idx, self.topk_w, self.counts, self.offsets, self.xp,
                            self.pos, self.src, stream)
 
+    def gate_route_dispatch(self, x, w_router, logits=None, T=None, stream=None):
+        T = x.shape[0] if T is None else T
+        moe_gate_route_dispatch(self.ctx, T, x, w_router, logits, self.topk_idx, self.topk_w, self.counts,
+                                self.offsets, self.xp, self.pos, self.src, stream)
+
     def expert_ffn(self, T, stream=None):
         moe_expert_ffn(self.ctx, T, self.xp, self.offsets, self.packed, self.h, self.y, stream)
 
@@ -331,6 +345,14 @@ class MoEPath:
                           share.seg_begin, share.seg_end, stream)
         moe_expert_ffn_segments(self.ctx, T, share.n, rows_hint, self.xp, share.seg_begin, share.seg_end,
                                 share.slot_expert, self.packed, self.h, self.y, stream)
+
+    def forward_from_gate(self, x, w_router, stream=None):
+        """One pass of the path that starts at the gating GEMM: x[T, d], w_router[E, d] float32."""
+        T = x.shape[0]
+        self.gate_route_dispatch(x, w_router, None, T, stream)
+        self.expert_ffn(T, stream)
+        self.combine(T, stream)
+        return self.out[:T]
 
     def forward(self, x, logits, stream=None):
         """One pass of the whole hot path; returns out[:T] (a view of the preallocated buffer)."""

@@ -195,6 +195,28 @@ moe_status moe_route_dispatch(moe_ctx* ctx, int32_t T, const float* logits, cons
   return finish(ctx, "moe_route_dispatch", err);
 }
 
+moe_status moe_gate_route_dispatch(moe_ctx* ctx, int32_t T, const void* x, const float* w_router, float* logits,
+                                   int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* offsets, void* xp,
+                                   int32_t* pos, int32_t* src, void* stream) {
+  const void* ptrs[] = {x, w_router, topk_idx, topk_w, counts, offsets, xp, pos, src};
+  const moe_status s = check_call(ctx, "moe_gate_route_dispatch", T, ptrs, 9);
+  if (s != MOE_OK) return s;
+  if (logits && !aligned16(logits))
+    return fail(ctx, MOE_ERR_INVALID_ARG, "moe_gate_route_dispatch: logits is not 16-byte aligned");
+  const moe_config& c = ctx->cfg;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int row_bytes = c.d * elem_bytes(ctx);
+  moe::launch_gate_topk_only(x, w_router, T, c.d, c.E, c.k, c.dtype, logits, topk_idx, topk_w, st);
+  hipError_t err = hipGetLastError();
+  if (err == hipSuccess &&
+      !moe::launch_dispatch_from_picks_fused(topk_idx, x, T, c.E, c.k, row_bytes, counts, offsets, xp, pos, src, st)) {
+    moe::launch_count(topk_idx, T, c.E, c.k, counts, offsets, st);
+    err = moe::launch_dispatch(x, topk_idx, offsets, T, c.E, c.k, row_bytes, xp, pos, src, st);
+  }
+  if (err == hipSuccess) err = hipGetLastError();
+  return finish(ctx, "moe_gate_route_dispatch", err);
+}
+
 moe_status moe_ffn_input(moe_ctx* ctx, int32_t T, const void* xp, const int32_t* offsets, const void* packed_w, void* h,
                          void* stream) {
   const void* ptrs[] = {xp, offsets, packed_w, h};

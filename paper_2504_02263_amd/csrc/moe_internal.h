@@ -19,6 +19,15 @@ hipError_t launch_route(const float* logits, int T, int E, int k, int32_t* topk_
                         int32_t* counts, int32_t* offsets, hipStream_t stream);
 hipError_t launch_gate_route(const void* x, const float* w_router, int T, int d, int E, int k, int dtype, float* logits,
                              int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* offsets, hipStream_t stream);
+// The gating GEMM with the top-k and the weights alone (one launch; T = 0: nothing), and the counting launch alone.
+void launch_gate_topk_only(const void* x, const float* w_router, int T, int d, int E, int k, int dtype, float* logits,
+                           int32_t* topk_idx, float* topk_w, hipStream_t stream);
+void launch_count(const int32_t* topk_idx, int T, int E, int k, int32_t* counts, int32_t* offsets, hipStream_t stream);
+// Counts, offsets and the dispatch pack from given picks in one launch when the batch is small enough
+// (false: nothing launched).
+bool launch_dispatch_from_picks_fused(const int32_t* topk_idx, const void* x, int T, int E, int k, int row_bytes,
+                                      int32_t* counts, int32_t* offsets, void* xp, int32_t* pos, int32_t* src,
+                                      hipStream_t stream);
 // Routing + dispatch pack in one launch when the batch is small enough; returns false (nothing
 // launched) when it is not, and the caller runs launch_route then launch_dispatch instead.
 bool launch_route_dispatch_fused(const float* logits, const void* x, int T, int E, int k, int row_bytes,

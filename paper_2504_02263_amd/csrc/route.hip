@@ -549,12 +549,14 @@ constexpr int kFusedMaxLogits = 8192;  // T * E floats staged in LDS
 
 // EM > 0 (E <= EM = 8 or 16): one lane owns a token and scans its E logits in registers, no
 // cross-lane traffic; EM = 0: the L-lane group of topk_group. Both give the same picks and weights.
-template <int L, int EM>
+// FROM_IDX: the picks are given (topk_idx is an input, written by the fused gating kernel just before)
+// and step 1 only stages them; logits and topk_w are not touched.
+template <int L, int EM, bool FROM_IDX = false>
 __global__ __launch_bounds__(256) void route_dispatch_small_kernel(
     const float* __restrict__ logits, const uint4* __restrict__ x, int T, int E, int k, int row_vecs,
     int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, int32_t* __restrict__ counts,
     int32_t* __restrict__ offsets, uint4* __restrict__ xp, int32_t* __restrict__ pos, int32_t* __restrict__ src) {
-  __shared__ float s_logits[kFusedMaxLogits];  // the whole logits matrix: one round of independent loads
+  __shared__ float s_logits[FROM_IDX ? 1 : kFusedMaxLogits];  // the whole logits matrix: one round of independent loads
   __shared__ int s_idx[kFusedMaxA];            // expert of assignment i = t * k + j
   __shared__ int s_src[kFusedMaxA];            // assignment that owns row r
   __shared__ int s_base[kMaxExperts];          // counts, then the next free row of each expert
@@ -565,6 +567,13 @@ __global__ __launch_bounds__(256) void route_dispatch_small_kernel(
   const int A = T * k;
 
   // 1. top-k of every token (256 / L tokens per pass)
+  if constexpr (FROM_IDX) {
+#pragma unroll 4
+    for (int i = tid; i < A; i += 256) {
+      const int e = topk_idx[i];
+      s_idx[i] = (unsigned)e < (unsigned)E ? e : 0;  // the gating kernel only writes experts in range
+    }
+  } else {
 #pragma unroll 8
   for (int u = tid; u < T * E; u += 256) s_logits[u] = logits[u];
   __syncthreads();
@@ -635,6 +644,7 @@ __global__ __launch_bounds__(256) void route_dispatch_small_kernel(
         }
       }
     }
+  }
   }
   s_base[tid] = 0;
   __syncthreads();
@@ -801,6 +811,20 @@ bool launch_route_dispatch_fused(const float* logits, const void* x, int T, int 
   return true;
 }
 
+// Counts, offsets and the dispatch pack from given picks in one launch (decode-sized batches); returns
+// false (nothing launched) when the batch is too large for it.
+bool launch_dispatch_from_picks_fused(const int32_t* topk_idx, const void* x, int T, int E, int k, int row_bytes,
+                                      int32_t* counts, int32_t* offsets, void* xp, int32_t* pos, int32_t* src,
+                                      hipStream_t stream) {
+  const int A = T * k;
+  if (T < 1 || T > kFusedMaxT || A > kFusedMaxA) return false;
+  const dim3 grid((A + 3) / 4 < 256 ? (A + 3) / 4 : 256), block(256);
+  hipLaunchKernelGGL((route_dispatch_small_kernel<8, 0, true>), grid, block, 0, stream, nullptr,
+                     static_cast<const uint4*>(x), T, E, k, row_bytes / 16, const_cast<int32_t*>(topk_idx), nullptr,
+                     counts, offsets, static_cast<uint4*>(xp), pos, src);
+  return true;
+}
+
 template <int TT, int EPT, int L>
 static void launch_gate_topk(bool bf16, hipStream_t stream, const void* x, const float* wr, int T, int d, int E, int k,
                              float* logits, int32_t* topk_idx, float* topk_w) {
@@ -815,6 +839,17 @@ static void launch_gate_topk(bool bf16, hipStream_t stream, const void* x, const
 
 hipError_t launch_gate_route(const void* x, const float* w_router, int T, int d, int E, int k, int dtype, float* logits,
                              int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* offsets, hipStream_t stream) {
+  launch_gate_topk_only(x, w_router, T, d, E, k, dtype, logits, topk_idx, topk_w, stream);
+  hipLaunchKernelGGL(route_count_kernel, dim3(1), dim3(1024), 0, stream, topk_idx, T * k, E, counts, offsets);
+  return hipGetLastError();
+}
+
+void launch_count(const int32_t* topk_idx, int T, int E, int k, int32_t* counts, int32_t* offsets, hipStream_t stream) {
+  hipLaunchKernelGGL(route_count_kernel, dim3(1), dim3(1024), 0, stream, topk_idx, T * k, E, counts, offsets);
+}
+
+void launch_gate_topk_only(const void* x, const float* w_router, int T, int d, int E, int k, int dtype, float* logits,
+                           int32_t* topk_idx, float* topk_w, hipStream_t stream) {
   if (T > 0) {
     const bool bf16 = dtype == MOE_BF16;
     const dim3 wgrid((T + 3) / 4);
@@ -857,8 +892,6 @@ hipError_t launch_gate_route(const void* x, const float* w_router, int T, int d,
     else if (E <= 128) launch_gate_topk<32, 16, 64>(bf16, stream, x, w_router, T, d, E, k, logits, topk_idx, topk_w);
     else launch_gate_topk<32, 32, 64>(bf16, stream, x, w_router, T, d, E, k, logits, topk_idx, topk_w);
   }
-  hipLaunchKernelGGL(route_count_kernel, dim3(1), dim3(1024), 0, stream, topk_idx, T * k, E, counts, offsets);
-  return hipGetLastError();
 }
 
 }  // namespace moe

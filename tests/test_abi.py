@@ -88,6 +88,8 @@ def test_hot_calls_reject_bad_arguments_before_launch():
         assert lib.moe_expert_ffn_segments(ctx, 4, 2, 0, good, good, good, None, good, good, good, None) == B.MOE_ERR_INVALID_ARG
         assert lib.moe_route_dispatch(ctx, 4, good, None, good, good, good, good, good, good, good, None) == B.MOE_ERR_INVALID_ARG
         assert lib.moe_route_dispatch(ctx, 65, good, good, good, good, good, good, good, good, good, None) == B.MOE_ERR_INVALID_ARG
+        assert lib.moe_gate_route_dispatch(ctx, 4, good, None, None, good, good, good, good, good, good, good, None) == B.MOE_ERR_INVALID_ARG
+        assert lib.moe_gate_route_dispatch(ctx, 4, good, good, good + 8, good, good, good, good, good, good, good, None) == B.MOE_ERR_INVALID_ARG
         # null context
         assert lib.moe_route(None, 4, good, good, good, good, good, None) == B.MOE_ERR_INVALID_ARG
     finally:

@@ -75,3 +75,13 @@ def test_default_run_carries_the_whole_curve():
     assert mb["workload"] == "finegrained_T8192" and [row["m"] for row in mb["rows"]] == [1, 2, 3, 4]
     assert all(row["two_stream_ms_per_step"] > 0 for row in mb["rows"])
     assert j["cpu_baseline"]["gflops"] > 0 and j["cpu_baseline"]["cores_source"]
+
+
+@pytest.mark.gpu
+def test_router_gate_times_the_layer_from_the_gating_gemm():
+    r = _run("--workload", "tiny_fp32", "--router", "gate", "--steps", "3", "--warmup", "1", "--cpu-sample-tokens", "64")
+    assert r.returncode == 0, r.stderr[-2000:]
+    j = json.loads([l for l in r.stdout.splitlines() if l.strip()][-1])
+    assert "gating GEMM" in j["config"]["router"]
+    assert {"gate_route", "gate_route_dispatch", "ffn_input", "ffn_output", "combine"} == set(j["layer"]["calls_ms"])
+    assert sum(j["config"]["tokens_per_expert"]) == j["config"]["T"] * j["config"]["k"]

@@ -570,3 +570,41 @@ def test_millions_of_assignments():
     path.close()
     with pytest.raises(B.MoeError):
         B.moe_create((1 << 22) // k + 1, d, f, E, k, "f32")          # one token more than the limit
+
+
+@pytest.mark.parametrize("T,d,E,k,dtype", [(64, 256, 8, 2, "f32"), (256, 6144, 8, 2, "bf16"), (257, 384, 16, 4, "bf16"),
+                                           (341, 512, 64, 6, "bf16"), (512, 128, 8, 4, "bf16"), (1000, 512, 64, 6, "bf16"),
+                                           (33, 256, 256, 8, "f32"), (1, 128, 5, 3, "bf16"), (2731, 256, 64, 6, "bf16")])
+def test_gate_route_dispatch_one_call(T, d, E, k, dtype):
+    """moe_gate_route_dispatch: from the token embeddings to the packed rows in one call (two launches at decode
+    sizes). The gate scores against the oracle's float64 product; everything after them bit-exact against the
+    oracle run on the very logits the GPU produced (two float32 sums in different order may flip a near-tie, so
+    exact routing is only defined on identical logits); and identical to moe_gate_route + moe_dispatch."""
+    cfg = small_cfg(T, d, 128, E, k, dtype)
+    x = synth.make_activations(cfg, 4)
+    w_r = synth.make_router_weight(cfg, 4)
+    a = B.MoEPath(T, d, 128, E, k, dtype)
+    b = B.MoEPath(T, d, 128, E, k, dtype)
+    xd, wd = dev(x), dev(w_r)
+    for p in (a, b):
+        for t in (p.topk_idx, p.pos, p.src, p.counts, p.offsets):
+            t.fill_(-7)
+        p.xp.zero_()
+    logits = torch.full((T, E), 7.0, dtype=torch.float32, device="cuda")
+    a.gate_route_dispatch(xd, wd, logits)
+    b.gate_route(xd, wd, None)
+    b.dispatch(xd)
+    torch.cuda.synchronize()
+    g_logits = host(logits)
+    ref_logits = O.gate_logits(x, w_r)
+    assert float(np.linalg.norm(g_logits - ref_logits.astype(np.float64)) / np.linalg.norm(ref_logits)) <= 1e-5
+    idx, w, counts, offsets = O.route(g_logits, k)
+    xp, pos, src = O.dispatch(x, idx, offsets)
+    check_integers(a, dict(topk_idx=idx, topk_w=w, counts=counts, offsets=offsets, xp=xp, pos=pos, src=src), T, k)
+    for name in ("topk_idx", "topk_w", "counts", "offsets", "xp", "pos", "src"):
+        assert torch.equal(getattr(a, name), getattr(b, name)), name
+    a.gate_route_dispatch(xd, wd, None)                    # without the logits output: same picks, same rows
+    torch.cuda.synchronize()
+    assert torch.equal(a.topk_idx, b.topk_idx) and torch.equal(a.src, b.src) and torch.equal(a.xp, b.xp)
+    a.close()
+    b.close()
