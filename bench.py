@@ -167,7 +167,8 @@ def time_workload(cfg, paths, x_d, logits_d, steps, warmup, torch, R, synth, bre
     step_flops = sum(R.layer_cost(q - p, cfg.d, cfg.f, cfg.E, cfg.k, s, active_experts=active).flops for p, q in ranges)
     step_min_bytes = sum(R.layer_cost(q - p, cfg.d, cfg.f, cfg.E, cfg.k, s, active_experts=active).layer_min_bytes
                          for p, q in ranges)
-    return dict(warm_steps=warm_steps, ms_per_step=ms_per_step, ffn_in_ms=ffn_in_ms, ffn_in_pct=ffn_in_pct, calls_ms=calls_ms, counts=counts, cost=launch_cost,
+    kernels = {"ffn_input": paths[0].ffn_kernel_name(T, 0), "ffn_output": paths[0].ffn_kernel_name(T, 1)}
+    return dict(kernels=kernels, warm_steps=warm_steps, ms_per_step=ms_per_step, ffn_in_ms=ffn_in_ms, ffn_in_pct=ffn_in_pct, calls_ms=calls_ms, counts=counts, cost=launch_cost,
                 step_flops=step_flops, step_min_bytes=step_min_bytes, serial_ms=serial_ms)
 
 
@@ -386,6 +387,7 @@ def result_line(cfg, steps, warmup, r, R, cpu, ceilings=None, router="logits"):
         "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "f": cfg.f, "E": cfg.E, "k": cfg.k,
                    "router": "gating GEMM x*W_r inside the timed step (moe_gate_route_dispatch)" if router == "gate"
                    else "logits given (moe_route_dispatch)",
+                   "ffn_kernel": r.get("kernels"),
                    "micro_batches": cfg.micro_batches, "load_skew_hint": round(synth_skew(cfg), 3),
                    "tokens_per_expert_mean": cfg.T * cfg.k / cfg.E / cfg.micro_batches,
                    "tokens_per_expert_max": int(counts.max()), "tokens_per_expert_min": int(counts.min()),

@@ -71,6 +71,12 @@ void moe_destroy(moe_ctx* ctx);
 const char* moe_last_error(const moe_ctx* ctx);
 const char* moe_status_string(moe_status s);
 
+/* Name of the GEMM kernel moe_ffn_input (stage 0) or moe_ffn_output (stage 1) launches for a batch of T tokens on
+ * this context: "streaming" (128-row tiles, weights read once, for decode-sized per-expert batches; Section 2.3's
+ * memory-bound side), "large-batch" (256-row tiles, matrix-core bound side) or "f32". A host-side query for
+ * reports; "" for bad arguments. */
+const char* moe_ffn_kernel_name(const moe_ctx* ctx, int32_t T, int32_t stage);
+
 /* Bytes of the packed expert-weight buffer moe_pack_weights writes (0 if cfg is invalid). */
 size_t moe_packed_weight_bytes(const moe_config* cfg);
 

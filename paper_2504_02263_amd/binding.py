@@ -22,7 +22,7 @@ MOE_OK, MOE_ERR_INVALID_ARG, MOE_ERR_UNSUPPORTED, MOE_ERR_HIP = 0, 1, 2, 3
 MOE_F32, MOE_BF16 = 0, 1
 _DTYPES = {"f32": (MOE_F32, torch.float32), "bf16": (MOE_BF16, torch.bfloat16)}
 
-EXPORTS = ("moe_create", "moe_destroy", "moe_last_error", "moe_status_string", "moe_packed_weight_bytes",
+EXPORTS = ("moe_create", "moe_destroy", "moe_last_error", "moe_status_string", "moe_ffn_kernel_name", "moe_packed_weight_bytes",
            "moe_pack_weights", "moe_route", "moe_gate_route", "moe_dispatch", "moe_expert_ffn", "moe_ffn_input", "moe_ffn_output",
            "moe_combine", "moe_plan_experts", "moe_slot_segments", "moe_expert_ffn_segments", "moe_route_dispatch",
            "moe_gate_route_dispatch", "moe_expert_ffn_static", "moe_probe_stream_read", "moe_probe_mfma")
@@ -62,6 +62,8 @@ def load_library() -> ctypes.CDLL:
     lib.moe_last_error.restype = ctypes.c_char_p
     lib.moe_status_string.argtypes = [ctypes.c_int]
     lib.moe_status_string.restype = ctypes.c_char_p
+    lib.moe_ffn_kernel_name.argtypes = [vp, i32, i32]
+    lib.moe_ffn_kernel_name.restype = ctypes.c_char_p
     lib.moe_packed_weight_bytes.argtypes = [cfgp]
     lib.moe_packed_weight_bytes.restype = ctypes.c_size_t
     lib.moe_pack_weights.argtypes = [vp] + [vp] * 4 + [vp]
@@ -137,6 +139,10 @@ def moe_create(T_max: int, d: int, f: int, E: int, k: int, dtype: str, load_skew
 
 def moe_destroy(ctx: int) -> None:
     load_library().moe_destroy(ctx)
+
+
+def moe_ffn_kernel_name(ctx, T: int, stage: int) -> str:
+    return load_library().moe_ffn_kernel_name(ctx, T, stage).decode()
 
 
 def moe_packed_weight_bytes(T_max: int, d: int, f: int, E: int, k: int, dtype: str) -> int:
@@ -323,6 +329,9 @@ class MoEPath:
         T = x.shape[0] if T is None else T
         moe_gate_route_dispatch(self.ctx, T, x, w_router, logits, self.topk_idx, self.topk_w, self.counts,
                                 self.offsets, self.xp, self.pos, self.src, stream)
+
+    def ffn_kernel_name(self, T, stage) -> str:
+        return moe_ffn_kernel_name(self.ctx, T, stage)
 
     def expert_ffn(self, T, stream=None):
         moe_expert_ffn(self.ctx, T, self.xp, self.offsets, self.packed, self.h, self.y, stream)

@@ -810,6 +810,14 @@ hipError_t launch_slot_segments(const int32_t* slot_expert, const int32_t* slot_
   return hipGetLastError();
 }
 
+constexpr int kStreamRows = 128;  // rows of the streaming kernel's tile
+
+bool ffn_picks_streaming(const moe_config& cfg, int stage, int n_segs, int rows_hint, int seg_rows_max) {
+  const int K = stage == 0 ? cfg.d : cfg.f;
+  const float mean = (cfg.load_skew >= 1.f ? cfg.load_skew : 1.f) * (float)rows_hint / (n_segs > 0 ? n_segs : 1);  // of a popular segment
+  return K < 256 || seg_rows_max <= kStreamRows || mean + 2.f * sqrtf(mean) <= (float)kStreamRows;
+}
+
 hipError_t launch_ffn_segments(const moe_config& cfg, int stage, const int32_t* seg_begin, const int32_t* seg_end,
                                const int32_t* seg_expert, int n_segs, int rows_bound, int rows_hint, int rows_cap,
                                int seg_rows_max, const void* in, const void* packed, void* out, hipStream_t stream) {
@@ -835,9 +843,7 @@ hipError_t launch_ffn_segments(const moe_config& cfg, int stage, const int32_t* 
     // the spread of a near-uniform router), or when no segment can be taller (seg_rows_max: an expert gets
     // at most one row per token). Measured: at 104 and 112 mean rows it is
     // 3 % faster, at 120 mean rows the large-batch kernel wins by 9 %.
-    constexpr int kStreamRows = 128;
-    const float mean = (cfg.load_skew >= 1.f ? cfg.load_skew : 1.f) * (float)rows_hint / n_segs;  // of a popular segment
-    const bool streaming = K < 256 || seg_rows_max <= kStreamRows || mean + 2.f * sqrtf(mean) <= (float)kStreamRows;
+    const bool streaming = ffn_picks_streaming(cfg, stage, n_segs, rows_hint, seg_rows_max);
     const char* w = static_cast<const char*>(packed) + (stage == 0 ? 0 : 2 * one * 2);
     if (streaming) {
       const int tiles = max_m_tiles(A, n_segs, kStreamRows);

@@ -132,6 +132,13 @@ const char* moe_status_string(moe_status s) {
   return "unknown moe_status";
 }
 
+const char* moe_ffn_kernel_name(const moe_ctx* ctx, int32_t T, int32_t stage) {
+  if (!ctx || T < 0 || (stage != 0 && stage != 1)) return "";
+  if (ctx->cfg.dtype != MOE_BF16) return "f32";
+  const int A = T * ctx->cfg.k;
+  return moe::ffn_picks_streaming(ctx->cfg, stage, ctx->cfg.E, A, T) ? "streaming" : "large-batch";
+}
+
 size_t moe_packed_weight_bytes(const moe_config* cfg) {
   const char* why;
   if (!cfg || check_config(cfg, &why) != MOE_OK) return 0;

@@ -49,6 +49,8 @@ hipError_t launch_ffn_stage(const moe_config& cfg, int stage, int T, const void*
 hipError_t launch_ffn_segments(const moe_config& cfg, int stage, const int32_t* seg_begin, const int32_t* seg_end,
                                const int32_t* seg_expert, int n_segs, int rows_bound, int rows_hint, int rows_cap,
                                int seg_rows_max, const void* in, const void* packed, void* out, hipStream_t stream);
+// Which bf16 GEMM kernel a launch of `stage` over n_segs segments runs (see launch_ffn_segments): true = streaming.
+bool ffn_picks_streaming(const moe_config& cfg, int stage, int n_segs, int rows_hint, int seg_rows_max);
 hipError_t launch_slot_segments(const int32_t* slot_expert, const int32_t* slot_copy, const int32_t* replicas,
                                 const int32_t* offsets, int n_slots, int E, int32_t* seg_begin, int32_t* seg_end,
                                 hipStream_t stream);
